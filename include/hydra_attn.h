@@ -1,0 +1,118 @@
+/*
+ * hydra_attn.h - C ABI of the packed variable-length attention library for MI355X (gfx950).
+ *
+ * The library implements the data-parallel computation that dominates the encode and prefill
+ * stages of a multimodal LLM served with stage-level batching (HydraInfer, Section 4.2,
+ * Algorithm 1): many images, or many requests, of different lengths are packed into one batch,
+ * and every attention layer then runs
+ *   - bidirectional attention inside each image (vision encoder, "encode" stage), or
+ *   - causal attention inside each request over its image tokens followed by its text tokens
+ *     (LLM "prefill" stage, Section 2.1: X = I || T, s = n + m), after which the request's K/V
+ *     are kept in a paged KV cache (block size 16 in Section 5.1) for the decode stage.
+ * The operation itself is scaled-dot-product attention as costed in the paper's Table 2 (rows
+ * Attention/encode, Attention/prefill) and its appendix on computation and memory access:
+ * multiply the query with the key, softmax, multiply with the value; 4*B*T^2*H FLOPs.
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *     frees or keeps them.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without synchronising with the device.
+ *   - bf16 means the upper 16 bits of an IEEE binary32 value.
+ *   - Return value: a hydra_status.  Argument errors are detected on the host before anything
+ *     is launched; nothing is written in that case.  The library neither prints nor aborts.
+ *   - The calls are re-entrant; there is no global mutable state.  Results are bit-identical
+ *     from run to run (no floating-point atomics; the order of the work list never affects the
+ *     value of any output element).
+ *   - Contents of device-side index arrays (cu_seqlens, slot_mapping) cannot be checked without
+ *     a device synchronisation; violating their documented preconditions is undefined behaviour.
+ */
+#ifndef HYDRA_ATTN_H
+#define HYDRA_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HYDRA_OK = 0,
+  HYDRA_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned pointer or stride, bad scale */
+  HYDRA_ERR_UNSUPPORTED = 2, /* head_dim not in {64, 80, 128}, or a size beyond the stated limits    */
+  HYDRA_ERR_WORKSPACE = 3,   /* workspace missing or smaller than hydra_attn_workspace_bytes()        */
+  HYDRA_ERR_LAUNCH = 4       /* the HIP runtime refused a launch                                     */
+} hydra_status;
+
+/*
+ * Packed variable-length attention, forward.
+ *
+ * For every sequence b with packed token range [cu_seqlens[b], cu_seqlens[b+1]) of length L, every
+ * query head h (KV head h / (n_q_heads / n_kv_heads), i.e. consecutive query heads share a KV head)
+ * and every local query index i:
+ *     J(i) = {0..L-1} if causal == 0, {0..i} if causal != 0      (indices local to the sequence)
+ *     z_j  = softmax_scale * <q[i,h,:], k[j,hk,:]>,  p = softmax over J(i),  out[i,h,:] = sum_j p_j v[j,hk,:]
+ * Tokens of different sequences never interact.  Arithmetic: bf16 inputs, both contractions on the
+ * bf16 matrix cores with fp32 accumulation, softmax in fp32, probabilities rounded to bf16 before
+ * the second contraction, output rounded to bf16 (round to nearest even).
+ *
+ *   q    bf16 [total_tokens, n_q_heads,  head_dim]   token stride q_token_stride  (elements)
+ *   k,v  bf16 [total_tokens, n_kv_heads, head_dim]   token strides k_/v_token_stride (elements)
+ *        the head stride is head_dim and head_dim is contiguous, so q/k/v may be views into one
+ *        fused QKV buffer.  Base pointers must be 16-byte aligned and strides multiples of 8.
+ *   out  bf16 [total_tokens, n_q_heads, head_dim], contiguous, 16-byte aligned; every element of
+ *        every token in [0, total_tokens) that belongs to a sequence is written.
+ *   cu_seqlens  device int32 [batch + 1]; cu_seqlens[0] == 0, non-decreasing, cu_seqlens[batch] ==
+ *        total_tokens, no sequence longer than max_seqlen.  Zero-length sequences are allowed.
+ *   max_seqlen  upper bound on the sequence lengths (>= 1); only used to size and order the work.
+ *   head_dim    64, 80 or 128.   n_q_heads % n_kv_heads == 0.
+ *   softmax_scale  finite and >= 0 (normally 1/sqrt(head_dim)).
+ *   workspace   device memory, 16-byte aligned, at least hydra_attn_workspace_bytes(...) bytes.  It
+ *        receives the tile work list built on the device from cu_seqlens (entries of
+ *        (sequence, KV head, first 64-query tile) ordered longest first).  It need not be
+ *        initialised and may be reused by the next call on the same stream.
+ *
+ * batch == 0 or total_tokens == 0 returns HYDRA_OK without launching.
+ */
+int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out,
+                          int64_t q_token_stride, int64_t k_token_stride, int64_t v_token_stride,
+                          const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                          int32_t causal, float softmax_scale,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Scatter of the prefill K/V of a packed batch into a paged KV cache (Section 5.1: KV-cache block
+ * size 16; the per-request page tables of Section 4.3 are flattened by the caller into one slot per
+ * token, slot = block_id * block_size + offset_in_block).
+ *
+ *   for t in [0, total_tokens): s = slot_mapping[t]; if s >= 0:
+ *       k_cache[s / block_size, s % block_size, :, :] = k[t, :, :]     (bit copy), same for v.
+ *
+ *   k, v       bf16 [total_tokens, n_kv_heads, head_dim], token strides in elements (multiples of 8),
+ *              16-byte aligned; may be views into a fused QKV buffer.
+ *   k_cache, v_cache  bf16 [num_blocks, block_size, n_kv_heads, head_dim], contiguous, 16-byte aligned.
+ *              Slots not named by slot_mapping keep their contents.
+ *   slot_mapping  device int64 [total_tokens]; each value is < 0 (token skipped) or in
+ *              [0, num_blocks * block_size) and no two tokens share a slot (otherwise undefined).
+ *   n_kv_heads * head_dim must be a multiple of 8 (rows are moved in 16-byte pieces).
+ *
+ * total_tokens == 0 returns HYDRA_OK without launching.
+ */
+int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, int64_t v_token_stride,
+                         void* k_cache, void* v_cache, const int64_t* slot_mapping,
+                         int32_t total_tokens, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t block_size, int64_t num_blocks, void* stream);
+
+/* Bytes of workspace hydra_attn_varlen_fwd needs for these sizes (0 if the sizes are invalid).
+ * Depends only on batch, total_tokens and the head counts; pure host arithmetic. */
+size_t hydra_attn_workspace_bytes(int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim);
+
+/* Static, NUL-terminated description of a hydra_status value. */
+const char* hydra_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYDRA_ATTN_H */

@@ -1,0 +1,11 @@
+"""MI355X-native packed variable-length attention + paged KV-cache write (gfx950 HIP kernels
+behind a C ABI; this package is only the thin Python binding)."""
+from .binding import (  # noqa: F401
+    HydraError,
+    hydra_attn_varlen_fwd,
+    hydra_attn_workspace_bytes,
+    hydra_kv_cache_write,
+    hydra_status_string,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,116 @@
+"""ctypes binding of include/hydra_attn.h.  Argument marshalling only: tensors in, raw device
+pointers and sizes out; every step of the computation runs in the HIP kernels.  There is no
+fallback: if the shared library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhydra_attn.so")
+_lib = None
+
+HYDRA_OK = 0
+
+
+class HydraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {hydra_status_string(status)} (status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library.  Raises if it has not been built (python -m paper_2505_12658_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2505_12658_amd.build`; "
+                              "there is no CPU or PyTorch fallback for this library")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        lib.hydra_attn_varlen_fwd.restype = ctypes.c_int
+        lib.hydra_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.c_float,
+                                              vp, sz, vp]
+        lib.hydra_kv_cache_write.restype = ctypes.c_int
+        lib.hydra_kv_cache_write.argtypes = [vp, vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, i64, vp]
+        lib.hydra_attn_workspace_bytes.restype = sz
+        lib.hydra_attn_workspace_bytes.argtypes = [i32] * 6
+        lib.hydra_status_string.restype = ctypes.c_char_p
+        lib.hydra_status_string.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def hydra_status_string(status: int) -> str:
+    return load_library().hydra_status_string(int(status)).decode()
+
+
+def hydra_attn_workspace_bytes(batch: int, total_tokens: int, max_seqlen: int, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:
+    return int(load_library().hydra_attn_workspace_bytes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim))
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _check_token_major(t: torch.Tensor, name: str):
+    if t.dtype != torch.bfloat16 or t.dim() != 3 or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA bf16 tensor [tokens, heads, head_dim]")
+    if t.stride(2) != 1 or t.stride(1) != t.shape[2]:
+        raise ValueError(f"{name}: head_dim must be contiguous and the head stride must equal head_dim")
+
+
+def hydra_attn_varlen_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, causal: bool,
+                          softmax_scale: float, out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """q [N, Hq, d], k/v [N, Hkv, d] bf16 (token-strided views allowed), cu_seqlens int32 [B+1] on the device."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _check_token_major(t, n)
+    if cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_cuda or not cu_seqlens.is_contiguous():
+        raise TypeError("cu_seqlens must be a contiguous CUDA int32 tensor")
+    N, Hq, d = q.shape
+    Hkv = k.shape[1]
+    batch = cu_seqlens.numel() - 1
+    if out is None:
+        out = torch.empty((N, Hq, d), dtype=torch.bfloat16, device=q.device)
+    elif not out.is_contiguous() or out.shape != (N, Hq, d) or out.dtype != torch.bfloat16:
+        raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    need = hydra_attn_workspace_bytes(batch, N, max_seqlen, Hq, Hkv, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    rc = lib.hydra_attn_varlen_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), q.stride(0), k.stride(0), v.stride(0),
+                                   cu_seqlens.data_ptr(), batch, N, int(max_seqlen), Hq, Hkv, d, int(bool(causal)), float(softmax_scale),
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_varlen_fwd")
+    return out
+
+
+def hydra_kv_cache_write(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, slot_mapping: torch.Tensor,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """k/v [N, Hkv, d] bf16; caches [num_blocks, block_size, Hkv, d] bf16 contiguous; slot_mapping int64 [N]."""
+    lib = load_library()
+    for t, n in ((k, "k"), (v, "v")):
+        _check_token_major(t, n)
+    if k_cache.dim() != 4 or not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape:
+        raise ValueError("caches must be contiguous [num_blocks, block_size, n_kv_heads, head_dim] of equal shape")
+    if k_cache.dtype != torch.bfloat16 or v_cache.dtype != torch.bfloat16 or not k_cache.is_cuda:
+        raise TypeError("caches must be CUDA bf16 tensors")
+    if slot_mapping.dtype != torch.int64 or not slot_mapping.is_cuda or not slot_mapping.is_contiguous():
+        raise TypeError("slot_mapping must be a contiguous CUDA int64 tensor")
+    N, Hkv, d = k.shape
+    if slot_mapping.numel() != N or tuple(k_cache.shape[2:]) != (Hkv, d) or v.shape != k.shape:
+        raise ValueError("shape mismatch between k/v, caches and slot_mapping")
+    rc = lib.hydra_kv_cache_write(k.data_ptr(), v.data_ptr(), k.stride(0), v.stride(0), k_cache.data_ptr(), v_cache.data_ptr(),
+                                  slot_mapping.data_ptr(), N, Hkv, d, k_cache.shape[1], k_cache.shape[0], _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_kv_cache_write")

@@ -1,0 +1,143 @@
+// C ABI of the library: argument validation on the host, then launches.  See include/hydra_attn.h
+// for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/hydra_attn.h"
+#include "attn_fwd.hpp"
+#include "kv_write.hpp"
+#include "worklist.hpp"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool head_dim_supported(int d) { return d == 64 || d == 80 || d == 128; }
+
+template <int D>
+hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned grid, hipStream_t stream) {
+  if (causal)
+    hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
+  else
+    hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, false>), dim3(grid), dim3(256), 0, stream, args);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hydra_attn_workspace_bytes(int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim) {
+  if (batch < 0 || total_tokens < 0 || max_seqlen < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 ||
+      !head_dim_supported(head_dim))
+    return 0;
+  return hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads).total;
+}
+
+const char* hydra_status_string(int status) {
+  switch (status) {
+    case HYDRA_OK: return "ok";
+    case HYDRA_ERR_INVALID_ARG: return "invalid argument";
+    case HYDRA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case HYDRA_ERR_WORKSPACE: return "workspace missing or too small";
+    case HYDRA_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
+                          int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (batch < 0 || total_tokens < 0 || n_q_heads <= 0 || n_kv_heads <= 0) return HYDRA_ERR_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return HYDRA_ERR_INVALID_ARG;
+  if (!head_dim_supported(head_dim)) return HYDRA_ERR_UNSUPPORTED;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
+  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
+  if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
+  if (max_seqlen < 1) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
+  if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
+      v_token_stride < (int64_t)n_kv_heads * head_dim)
+    return HYDRA_ERR_INVALID_ARG;
+  if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
+  // 32-bit index arithmetic inside the prepass
+  if ((int64_t)n_q_heads * ((int64_t)total_tokens / hydra::kWaveTileRows + batch) > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
+
+  const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
+  if (!workspace || workspace_bytes < lay.total || !aligned16(workspace)) return HYDRA_ERR_WORKSPACE;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int32_t* n_items = reinterpret_cast<int32_t*>(ws);
+  int32_t* item_offset = reinterpret_cast<int32_t*>(ws + lay.offsets_at);
+  hydra::WorkItem* items = reinterpret_cast<hydra::WorkItem*>(ws + lay.items_at);
+  const int group = n_q_heads / n_kv_heads;
+
+  if (causal)
+    hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
+                       group, n_items, item_offset, items, (int)lay.capacity);
+  else
+    hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
+                       group, n_items, item_offset, items, (int)lay.capacity);
+  if (hipGetLastError() != hipSuccess) return HYDRA_ERR_LAUNCH;
+
+  hydra::AttnArgs args;
+  args.q = static_cast<const uint16_t*>(q);
+  args.k = static_cast<const uint16_t*>(k);
+  args.v = static_cast<const uint16_t*>(v);
+  args.out = static_cast<uint16_t*>(out);
+  args.q_stride = q_token_stride;
+  args.k_stride = k_token_stride;
+  args.v_stride = v_token_stride;
+  args.cu_seqlens = cu_seqlens;
+  args.items = items;
+  args.n_items = n_items;
+  args.n_q_heads = n_q_heads;
+  args.group = group;
+  args.scale_log2 = softmax_scale * 1.44269504088896340736f;
+
+  const unsigned grid = (unsigned)lay.capacity;
+  hipError_t err;
+  switch (head_dim) {
+    case 64: err = launch_attn<64>(causal != 0, args, grid, s); break;
+    case 80: err = launch_attn<80>(causal != 0, args, grid, s); break;
+    default: err = launch_attn<128>(causal != 0, args, grid, s); break;
+  }
+  return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, int64_t v_token_stride, void* k_cache, void* v_cache,
+                         const int64_t* slot_mapping, int32_t total_tokens, int32_t n_kv_heads, int32_t head_dim, int32_t block_size,
+                         int64_t num_blocks, void* stream) {
+  if (total_tokens < 0 || n_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks < 0) return HYDRA_ERR_INVALID_ARG;
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  if (row % 8 != 0) return HYDRA_ERR_UNSUPPORTED;
+  if (row > ((int64_t)1 << 24)) return HYDRA_ERR_UNSUPPORTED;
+  if (total_tokens == 0) return HYDRA_OK;
+  if (!k || !v || !k_cache || !v_cache || !slot_mapping) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache)) return HYDRA_ERR_INVALID_ARG;
+  if (k_token_stride < row || v_token_stride < row || ((k_token_stride | v_token_stride) & 7)) return HYDRA_ERR_INVALID_ARG;
+
+  hydra::KvWriteArgs args;
+  args.k = static_cast<const uint4*>(k);
+  args.v = static_cast<const uint4*>(v);
+  args.k_cache = static_cast<uint4*>(k_cache);
+  args.v_cache = static_cast<uint4*>(v_cache);
+  args.slot_mapping = slot_mapping;
+  args.k_stride16 = k_token_stride / 8;
+  args.v_stride16 = v_token_stride / 8;
+  args.total_tokens = total_tokens;
+  args.row16 = (int32_t)(row / 8);
+
+  const int64_t pieces = (int64_t)total_tokens * args.row16;
+  int64_t blocks = (pieces + hydra::kKvWriteThreads - 1) / hydra::kKvWriteThreads;
+  const int64_t max_blocks = 256 * 32;  // grid-stride beyond this
+  if (blocks > max_blocks) blocks = max_blocks;
+  hipLaunchKernelGGL(hydra::kv_cache_write_kernel, dim3((unsigned)blocks), dim3(hydra::kKvWriteThreads), 0, static_cast<hipStream_t>(stream), args);
+  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,40 @@
+// Paged KV-cache scatter: K/V rows of the packed prefill batch -> cache[slot_mapping[t]].
+// Pure data movement (HBM-bound): every lane moves one 16-byte piece with a 128-bit load and a
+// 128-bit store; the lanes of a row are consecutive, so both sides are fully coalesced even
+// though consecutive tokens land in unrelated pages (block size 16, Section 5.1 of the paper).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hydra {
+
+struct KvWriteArgs {
+  const uint4* k;
+  const uint4* v;
+  uint4* k_cache;
+  uint4* v_cache;
+  const int64_t* slot_mapping;
+  int64_t k_stride16, v_stride16;  // token strides in 16-byte units
+  int32_t total_tokens;
+  int32_t row16;                   // 16-byte pieces per token row (n_kv_heads * head_dim / 8)
+};
+
+constexpr int kKvWriteThreads = 256;
+
+// One thread per 16-byte piece of a token row; K and V handled by the same thread.
+__global__ __launch_bounds__(kKvWriteThreads) void kv_cache_write_kernel(const KvWriteArgs a) {
+  const int64_t total = (int64_t)a.total_tokens * a.row16;
+  const int64_t step = (int64_t)gridDim.x * kKvWriteThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kKvWriteThreads + threadIdx.x; i < total; i += step) {
+    const int32_t t = (int32_t)(i / a.row16);
+    const int32_t piece = (int32_t)(i - (int64_t)t * a.row16);
+    const int64_t slot = a.slot_mapping[t];
+    if (slot < 0) continue;
+    const uint4 kk = a.k[t * a.k_stride16 + piece];
+    const uint4 vv = a.v[t * a.v_stride16 + piece];
+    a.k_cache[slot * a.row16 + piece] = kk;
+    a.v_cache[slot * a.row16 + piece] = vv;
+  }
+}
+
+}  // namespace hydra

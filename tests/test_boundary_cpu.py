@@ -1,0 +1,111 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_12658_amd as hydra
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hydra.library_path()):
+        from paper_2505_12658_amd import build
+
+        build.build()
+    return hydra.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hydra_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hydra_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_symbols()
+    assert names == ["hydra_attn_varlen_fwd", "hydra_attn_workspace_bytes", "hydra_kv_cache_write", "hydra_status_string"]
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    assert hydra.hydra_status_string(0) == "ok"
+    assert len({hydra.hydra_status_string(i) for i in range(5)}) == 5
+    assert hydra.hydra_status_string(99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    assert hydra.hydra_attn_workspace_bytes(4, 438, 257, 2, 2, 64) > 0
+    assert hydra.hydra_attn_workspace_bytes(4, 438, 257, 3, 2, 64) == 0  # heads not divisible
+    assert hydra.hydra_attn_workspace_bytes(4, 438, 257, 2, 2, 96) == 0  # unsupported head_dim
+    assert hydra.hydra_attn_workspace_bytes(-1, 438, 257, 2, 2, 64) == 0
+    # grows with tokens and heads
+    a = hydra.hydra_attn_workspace_bytes(48, 30000, 1312, 28, 4, 128)
+    b = hydra.hydra_attn_workspace_bytes(48, 60000, 1312, 28, 4, 128)
+    assert b > a > 0
+
+
+def _attn(lib, q=16, k=16, v=16, out=16, qs=128, ks=128, vs=128, cu=16, batch=1, total=8, max_len=8, hq=2, hkv=2, d=64, causal=0,
+          scale=0.125, ws=16, ws_bytes=1 << 20, stream=None):
+    # fake, never dereferenced device addresses: every case below must be rejected on the host
+    return lib.hydra_attn_varlen_fwd(q, k, v, out, qs, ks, vs, cu, batch, total, max_len, hq, hkv, d, causal, scale, ws, ws_bytes, stream)
+
+
+def test_attn_argument_errors(lib):
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    assert _attn(lib, q=None) == INVALID
+    assert _attn(lib, out=None) == INVALID
+    assert _attn(lib, cu=None) == INVALID
+    assert _attn(lib, batch=-1) == INVALID
+    assert _attn(lib, total=-5) == INVALID
+    assert _attn(lib, hq=3, hkv=2) == INVALID
+    assert _attn(lib, hkv=0) == INVALID
+    assert _attn(lib, d=96) == UNSUPPORTED
+    assert _attn(lib, d=0) == UNSUPPORTED
+    assert _attn(lib, q=8) == INVALID  # misaligned
+    assert _attn(lib, qs=132) == INVALID  # stride not a multiple of 8 elements
+    assert _attn(lib, ks=64) == INVALID  # stride smaller than a token row
+    assert _attn(lib, scale=-1.0) == INVALID
+    assert _attn(lib, scale=float("nan")) == INVALID
+    assert _attn(lib, scale=float("inf")) == INVALID
+    assert _attn(lib, max_len=0) == INVALID
+    assert _attn(lib, ws=None) == WORKSPACE
+    assert _attn(lib, ws_bytes=8) == WORKSPACE
+    assert _attn(lib, ws=24) == WORKSPACE  # misaligned workspace
+    # empty batches succeed without touching any pointer
+    assert _attn(lib, batch=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0
+    assert _attn(lib, total=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0
+
+
+def _kvw(lib, k=16, v=16, ks=128, vs=128, kc=16, vc=16, slots=16, total=4, hkv=2, d=64, bs=16, nb=4, stream=None):
+    return lib.hydra_kv_cache_write(k, v, ks, vs, kc, vc, slots, total, hkv, d, bs, nb, stream)
+
+
+def test_kv_write_argument_errors(lib):
+    INVALID, UNSUPPORTED = 1, 2
+    assert _kvw(lib, k=None) == INVALID
+    assert _kvw(lib, vc=None) == INVALID
+    assert _kvw(lib, slots=None) == INVALID
+    assert _kvw(lib, total=-1) == INVALID
+    assert _kvw(lib, bs=0) == INVALID
+    assert _kvw(lib, hkv=0) == INVALID
+    assert _kvw(lib, nb=-1) == INVALID
+    assert _kvw(lib, hkv=1, d=4) == UNSUPPORTED  # row not a multiple of 16 bytes
+    assert _kvw(lib, kc=4) == INVALID
+    assert _kvw(lib, ks=64) == INVALID
+    assert _kvw(lib, vs=132) == INVALID
+    assert _kvw(lib, total=0, k=None, v=None, kc=None, vc=None, slots=None) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2505_12658_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()
