@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed varlen attention + paged KV write path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: the device work-list build,
+the fused attention kernel and (for prefill workloads) the paged KV scatter.  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA, 256 CUs x 4096 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+HEADLINE = "qwen2vl_7b_prefill"
+OTHERS = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode"]
+
+
+class DeviceBatch:
+    """One workload resident on the GPU, with `n_sets` rotating copies of every buffer so that
+    consecutive steps do not find their Q/K/V/O in the 256 MB last-level cache."""
+
+    def __init__(self, w: si.Workload, n_sets: int, dev):
+        import paper_2505_12658_amd as hydra
+
+        self.hydra = hydra
+        self.w = w
+        self.dev = dev
+        q, k, v = si.make_qkv(w)
+        self.host_qkv = (q, k, v)
+        self.cu = torch.from_numpy(w.cu_seqlens).to(dev)
+        self.sets = []
+        for i in range(n_sets):
+            s = {"q": q.to(dev), "k": k.to(dev), "v": v.to(dev), "out": torch.empty(q.shape, dtype=torch.bfloat16, device=dev)}
+            if w.kv_cache:
+                slots, nb = si.make_slot_mapping(w.lengths, w.block_size, spare_blocks=8, seed=w.seed + i)
+                s["slots"] = torch.from_numpy(slots).to(dev)
+                s["k_cache"] = torch.zeros((nb, w.block_size, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+                s["v_cache"] = torch.zeros_like(s["k_cache"])
+            self.sets.append(s)
+        need = hydra.hydra_attn_workspace_bytes(w.batch, w.total_tokens, w.max_seqlen, w.n_q_heads, w.n_kv_heads, w.head_dim)
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    def step(self, i: int, events=None):
+        h, w, s = self.hydra, self.w, self.sets[i % len(self.sets)]
+        h.hydra_attn_build_worklist(self.cu, w.total_tokens, w.max_seqlen, w.n_q_heads, w.n_kv_heads, w.head_dim, w.causal, self.ws)
+        if events is not None:
+            events[0].record()
+        h.hydra_attn_varlen_fwd_prebuilt(s["q"], s["k"], s["v"], self.cu, w.max_seqlen, w.causal, w.softmax_scale, s["out"], self.ws)
+        if events is not None:
+            events[1].record()
+        if w.kv_cache:
+            h.hydra_kv_cache_write(s["k"], s["v"], s["k_cache"], s["v_cache"], s["slots"])
+            if events is not None:
+                events[2].record()
+
+
+def time_steps(batch: DeviceBatch, steps: int, warmup: int):
+    """Wall-clock over exactly `steps` steps, bracketed by device synchronisation."""
+    for i in range(warmup):
+        batch.step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        batch.step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_kernels(batch: DeviceBatch, steps: int):
+    """Same steps again with HIP events (on the launch stream) around the attention kernel and the
+    KV scatter.  Returns average attention-kernel and KV-write durations in seconds."""
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        batch.step(i, evs[i])
+    torch.cuda.synchronize()
+    attn = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
+    kvw = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3 if batch.w.kv_cache else None
+    return attn, kvw
+
+
+def cpu_baseline(w: si.Workload, host_qkv, budget_s: float = 15.0):
+    """The fp64 oracle as it stands, on the host cores, on a bounded sample of the same workload:
+    whole sequences (all heads) taken in a seeded shuffled order until the estimated time reaches
+    the budget."""
+    from oracle import c_oracle, reference
+
+    q, k, v = (reference.bf16_bits_to_f64(si.bf16_bits(t)) for t in host_qkv)
+    cu = w.cu_seqlens
+    order = np.random.default_rng(1).permutation(w.batch)
+
+    def sub_batch(seqs):
+        idx = np.concatenate([np.arange(cu[b], cu[b + 1]) for b in seqs])
+        lens = [int(cu[b + 1] - cu[b]) for b in seqs]
+        return q[idx], k[idx], v[idx], np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), lens
+
+    def flops(lens):
+        pairs = sum(L * (L + 1) // 2 for L in lens) if w.causal else sum(L * L for L in lens)
+        return 4 * w.head_dim * w.n_q_heads * pairs
+
+    # calibration on the shortest sequence
+    shortest = [int(np.argmin(np.diff(cu)))]
+    qs, ks, vs, cus, lens = sub_batch(shortest)
+    t0 = time.perf_counter()
+    _, threads = c_oracle.attn_varlen(qs, ks, vs, cus, w.causal, w.softmax_scale, return_threads=True)
+    rate = flops(lens) / max(time.perf_counter() - t0, 1e-6)
+    chosen, total = [], 0.0
+    for b in order:
+        f = flops([int(cu[b + 1] - cu[b])])
+        if chosen and (total + f) / rate > budget_s:
+            break
+        chosen.append(int(b))
+        total += f
+    qs, ks, vs, cus, lens = sub_batch(chosen)
+    t0 = time.perf_counter()
+    _, threads = c_oracle.attn_varlen(qs, ks, vs, cus, w.causal, w.softmax_scale, return_threads=True)
+    dt = time.perf_counter() - t0
+    return {
+        "value": flops(lens) / dt * 1e-12,
+        "unit": "TFLOP/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"{len(chosen)} of {w.batch} sequences ({sum(lens)} of {w.total_tokens} tokens), all {w.n_q_heads} heads, "
+                  f"{flops(lens):.3e} FLOP in {dt:.2f} s, fp64 plain C + OpenMP",
+        "seconds": dt,
+    }
+
+
+def describe(w: si.Workload):
+    return {
+        "workload": w.name,
+        "sequences": w.batch,
+        "total_tokens": w.total_tokens,
+        "max_seqlen": w.max_seqlen,
+        "n_q_heads": w.n_q_heads,
+        "n_kv_heads": w.n_kv_heads,
+        "head_dim": w.head_dim,
+        "causal": w.causal,
+        "kv_block_size": w.block_size if w.kv_cache else None,
+        "seed": w.seed,
+        "attention_flops": w.attention_flops(),
+        "flop_convention": "4*head_dim*n_q_heads*visible (q,k) pairs",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=HEADLINE, choices=sorted(si.WORKLOADS))
+    ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (cold last-level cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (sequences are independent, so more GPUs would each take a "
+              "share of the batch with no exchange); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = si.WORKLOADS[args.workload]()
+    batch = DeviceBatch(w, args.sets, dev)
+    sec_per_step = time_steps(batch, args.steps, args.warmup)
+    attn_t, kvw_t = time_kernels(batch, args.steps)
+    flops = w.attention_flops()
+    attn_avg = float(attn_t.mean())
+    achieved = flops / attn_avg * 1e-12
+
+    result = {
+        "metric": "attention TFLOP/s and % of bf16 MFMA peak, packed varlen encode+prefill",
+        "value": flops / sec_per_step * 1e-12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": describe(w),
+        "step": "work-list build + fused attention" + (" + paged KV write" if w.kv_cache else ""),
+        "pct_of_bf16_mfma_peak": 100.0 * flops / sec_per_step * 1e-12 / PEAK_BF16_TFLOPS,
+        "buffer_sets": args.sets,
+        "roofline": {
+            "kernel": "attn_fwd_kernel",
+            "bound": "mfma",
+            "achieved": achieved,
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS,
+            "traffic": None,
+            "avg_kernel_us": attn_avg * 1e6,
+            "min_kernel_us": float(attn_t.min()) * 1e6,
+            "hbm_floor_us": w.attention_min_bytes() / (PEAK_HBM_GBS * 1e9) * 1e6,
+            "algorithmic_bytes": w.attention_min_bytes(),
+        },
+    }
+    if kvw_t is not None:
+        gbs = w.kv_write_bytes() / float(kvw_t.mean()) * 1e-9
+        result["kv_write"] = {"kernel": "kv_cache_write_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                              "frac": gbs / PEAK_HBM_GBS, "avg_kernel_us": float(kvw_t.mean()) * 1e6, "bytes": w.kv_write_bytes()}
+    host_qkv = batch.host_qkv
+    del batch
+    torch.cuda.empty_cache()
+
+    if not args.no_others:
+        others = []
+        for name in OTHERS:
+            ow = si.WORKLOADS[name]()
+            ob = DeviceBatch(ow, args.sets, dev)
+            sps = time_steps(ob, max(20, args.steps // 4), 5)
+            at, kt = time_kernels(ob, max(20, args.steps // 4))
+            f = ow.attention_flops()
+            entry = {"workload": name, "ms_per_step": sps * 1e3, "attn_kernel_us": float(at.mean()) * 1e6,
+                     "attn_tflops": f / float(at.mean()) * 1e-12, "frac_mfma_peak": f / float(at.mean()) * 1e-12 / PEAK_BF16_TFLOPS,
+                     "frac_hbm_peak": ow.attention_min_bytes() / float(at.mean()) * 1e-9 / PEAK_HBM_GBS}
+            if kt is not None:
+                entry["kv_write_gbs"] = ow.kv_write_bytes() / float(kt.mean()) * 1e-9
+            others.append(entry)
+            del ob
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, host_qkv)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

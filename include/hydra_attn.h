@@ -82,6 +82,29 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The two halves of hydra_attn_varlen_fwd, for callers that run many layers over one packed batch:
+ * the work list depends only on cu_seqlens, the head counts and the causal flag, so it can be built
+ * once per batch (the paper's Request Processor prepares such control parameters ahead of the GPU
+ * work, Section 4.1) and reused by the attention call of every layer.
+ *
+ * hydra_attn_build_worklist writes the work list for (cu_seqlens, n_q_heads, n_kv_heads, causal)
+ * into `workspace` (same size rule as above).  hydra_attn_varlen_fwd_prebuilt runs the attention
+ * kernel against a workspace filled by an earlier hydra_attn_build_worklist call on the same stream
+ * (or one that has completed) with the SAME batch, total_tokens, head counts and causal flag; it
+ * only reads the workspace.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
+ */
+int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, void* out,
+                                   int64_t q_token_stride, int64_t k_token_stride, int64_t v_token_stride,
+                                   const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                   int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                   int32_t causal, float softmax_scale,
+                                   const void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Scatter of the prefill K/V of a packed batch into a paged KV cache (Section 5.1: KV-cache block
  * size 16; the per-request page tables of Section 4.3 are flattened by the caller into one slot per
  * token, slot = block_id * block_size + offset_in_block).

@@ -2,7 +2,9 @@
 behind a C ABI; this package is only the thin Python binding)."""
 from .binding import (  # noqa: F401
     HydraError,
+    hydra_attn_build_worklist,
     hydra_attn_varlen_fwd,
+    hydra_attn_varlen_fwd_prebuilt,
     hydra_attn_workspace_bytes,
     hydra_kv_cache_write,
     hydra_status_string,

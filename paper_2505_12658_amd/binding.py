@@ -38,6 +38,10 @@ def load_library() -> ctypes.CDLL:
         lib.hydra_attn_varlen_fwd.restype = ctypes.c_int
         lib.hydra_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.c_float,
                                               vp, sz, vp]
+        lib.hydra_attn_varlen_fwd_prebuilt.restype = ctypes.c_int
+        lib.hydra_attn_varlen_fwd_prebuilt.argtypes = lib.hydra_attn_varlen_fwd.argtypes
+        lib.hydra_attn_build_worklist.restype = ctypes.c_int
+        lib.hydra_attn_build_worklist.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         lib.hydra_kv_cache_write.restype = ctypes.c_int
         lib.hydra_kv_cache_write.argtypes = [vp, vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, i64, vp]
         lib.hydra_attn_workspace_bytes.restype = sz
@@ -92,6 +96,43 @@ def hydra_attn_varlen_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_attn_varlen_fwd")
+    return out
+
+
+def hydra_attn_build_worklist(cu_seqlens: torch.Tensor, total_tokens: int, max_seqlen: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                              causal: bool, workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Builds the tile work list for one packed batch into `workspace` (allocated if None) and returns it."""
+    lib = load_library()
+    if cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_cuda or not cu_seqlens.is_contiguous():
+        raise TypeError("cu_seqlens must be a contiguous CUDA int32 tensor")
+    batch = cu_seqlens.numel() - 1
+    if workspace is None:
+        need = hydra_attn_workspace_bytes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=cu_seqlens.device)
+    rc = lib.hydra_attn_build_worklist(cu_seqlens.data_ptr(), batch, int(total_tokens), int(max_seqlen), n_q_heads, n_kv_heads, head_dim,
+                                       int(bool(causal)), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                       _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_build_worklist")
+    return workspace
+
+
+def hydra_attn_varlen_fwd_prebuilt(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int,
+                                   causal: bool, softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor,
+                                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Attention against a work list built earlier by hydra_attn_build_worklist for the same batch."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _check_token_major(t, n)
+    N, Hq, d = q.shape
+    if not out.is_contiguous() or out.shape != (N, Hq, d) or out.dtype != torch.bfloat16:
+        raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    rc = lib.hydra_attn_varlen_fwd_prebuilt(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), q.stride(0), k.stride(0),
+                                            v.stride(0), cu_seqlens.data_ptr(), cu_seqlens.numel() - 1, N, int(max_seqlen), Hq,
+                                            k.shape[1], d, int(bool(causal)), float(softmax_scale), workspace.data_ptr(),
+                                            workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_varlen_fwd_prebuilt")
     return out
 
 

@@ -47,27 +47,35 @@ const char* hydra_status_string(int status) {
   }
 }
 
-int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
-                          int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
-                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+namespace {
+
+// Argument checks shared by the three attention entry points.  `need_tensors` is false for the
+// work-list builder, which touches only cu_seqlens and the workspace.
+int check_attn_sizes(int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim) {
   if (batch < 0 || total_tokens < 0 || n_q_heads <= 0 || n_kv_heads <= 0) return HYDRA_ERR_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return HYDRA_ERR_INVALID_ARG;
   if (!head_dim_supported(head_dim)) return HYDRA_ERR_UNSUPPORTED;
-  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
-  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
-  if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
-  if (max_seqlen < 1) return HYDRA_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
-  if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
-      v_token_stride < (int64_t)n_kv_heads * head_dim)
-    return HYDRA_ERR_INVALID_ARG;
-  if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
+  if (batch > 0 && total_tokens > 0 && max_seqlen < 1) return HYDRA_ERR_INVALID_ARG;
   // 32-bit index arithmetic inside the prepass
   if ((int64_t)n_q_heads * ((int64_t)total_tokens / hydra::kWaveTileRows + batch) > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
+  return HYDRA_OK;
+}
 
-  const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
+int check_workspace(const void* workspace, size_t workspace_bytes, const hydra::WorkspaceLayout& lay) {
   if (!workspace || workspace_bytes < lay.total || !aligned16(workspace)) return HYDRA_ERR_WORKSPACE;
+  return HYDRA_OK;
+}
+
+}  // namespace
+
+int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t head_dim, int32_t causal, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
+  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
+  if (!cu_seqlens) return HYDRA_ERR_INVALID_ARG;
+  const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
+  if (int rc = check_workspace(workspace, workspace_bytes, lay)) return rc;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -75,15 +83,32 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
   int32_t* item_offset = reinterpret_cast<int32_t*>(ws + lay.offsets_at);
   hydra::WorkItem* items = reinterpret_cast<hydra::WorkItem*>(ws + lay.items_at);
   const int group = n_q_heads / n_kv_heads;
-
   if (causal)
     hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
                        group, n_items, item_offset, items, (int)lay.capacity);
   else
     hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
                        group, n_items, item_offset, items, (int)lay.capacity);
-  if (hipGetLastError() != hipSuccess) return HYDRA_ERR_LAUNCH;
+  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
 
+int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride,
+                                   int64_t k_token_stride, int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch,
+                                   int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                   int32_t causal, float softmax_scale, const void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
+  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
+  if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
+  if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
+      v_token_stride < (int64_t)n_kv_heads * head_dim)
+    return HYDRA_ERR_INVALID_ARG;
+  if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
+  const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
+  if (int rc = check_workspace(workspace, workspace_bytes, lay)) return rc;
+
+  const unsigned char* ws = static_cast<const unsigned char*>(workspace);
   hydra::AttnArgs args;
   args.q = static_cast<const uint16_t*>(q);
   args.k = static_cast<const uint16_t*>(k);
@@ -93,13 +118,15 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
   args.k_stride = k_token_stride;
   args.v_stride = v_token_stride;
   args.cu_seqlens = cu_seqlens;
-  args.items = items;
-  args.n_items = n_items;
+  args.items = reinterpret_cast<const hydra::WorkItem*>(ws + lay.items_at);
+  args.n_items = reinterpret_cast<const int32_t*>(ws);
   args.n_q_heads = n_q_heads;
-  args.group = group;
+  args.group = n_q_heads / n_kv_heads;
   args.scale_log2 = softmax_scale * 1.44269504088896340736f;
 
+  (void)causal;
   const unsigned grid = (unsigned)lay.capacity;
+  hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err;
   switch (head_dim) {
     case 64: err = launch_attn<64>(causal != 0, args, grid, s); break;
@@ -107,6 +134,30 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
     default: err = launch_attn<128>(causal != 0, args, grid, s); break;
   }
   return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
+                          int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  // validate everything before the first launch, so that an error never leaves half the work enqueued
+  if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
+  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
+  if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
+  if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
+      v_token_stride < (int64_t)n_kv_heads * head_dim)
+    return HYDRA_ERR_INVALID_ARG;
+  if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
+  if (int rc = check_workspace(workspace, workspace_bytes, hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads))) return rc;
+
+  if (int rc = hydra_attn_build_worklist(cu_seqlens, batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim, causal, workspace,
+                                         workspace_bytes, stream))
+    return rc;
+  return hydra_attn_varlen_fwd_prebuilt(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens,
+                                        max_seqlen, n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, workspace, workspace_bytes,
+                                        stream);
 }
 
 int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, int64_t v_token_stride, void* k_cache, void* v_cache,

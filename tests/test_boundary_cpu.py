@@ -28,7 +28,8 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert names == ["hydra_attn_varlen_fwd", "hydra_attn_workspace_bytes", "hydra_kv_cache_write", "hydra_status_string"]
+    assert names == ["hydra_attn_build_worklist", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
+                     "hydra_kv_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
 
