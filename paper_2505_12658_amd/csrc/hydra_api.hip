@@ -122,7 +122,10 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   args.n_items = reinterpret_cast<const int32_t*>(ws);
   args.n_q_heads = n_q_heads;
   args.group = n_q_heads / n_kv_heads;
-  args.scale_log2 = softmax_scale * 1.44269504088896340736f;
+  // A scale of exactly 0 is replaced by a vanishing positive one: every visible key still gets
+  // weight exp2(~0) = 1, while -inf (masked) times the scale stays -inf instead of becoming NaN.
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;
 
   (void)causal;
   const unsigned grid = (unsigned)lay.capacity;
