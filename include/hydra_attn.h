@@ -90,8 +90,10 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
  * hydra_attn_build_worklist writes the work list for (cu_seqlens, n_q_heads, n_kv_heads, causal)
  * into `workspace` (same size rule as above).  hydra_attn_varlen_fwd_prebuilt runs the attention
  * kernel against a workspace filled by an earlier hydra_attn_build_worklist call on the same stream
- * (or one that has completed) with the SAME batch, total_tokens, head counts and causal flag; it
- * only reads the workspace.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
+ * (or one that has completed) with the SAME batch, total_tokens, head counts and causal flag.  It
+ * reads the work list and uses a small flag array inside the workspace (left all-zero again when
+ * the call's work completes), so two attention calls that share one workspace must not overlap in
+ * time.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
  */
 int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal,
@@ -102,7 +104,7 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
                                    const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
                                    int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                    int32_t causal, float softmax_scale,
-                                   const void* workspace, size_t workspace_bytes, void* stream);
+                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Scatter of the prefill K/V of a packed batch into a paged KV cache (Section 5.1: KV-cache block

@@ -3,9 +3,14 @@
 // One workgroup (4 wavefronts, one per SIMD, up to 512 registers each) runs one work-list item:
 // up to four "wave tiles" that share a sequence and a KV head.  A wave tile is 64 consecutive
 // query tokens of one query head.  K/V tiles of 64 keys stream global -> LDS with direct-to-LDS
-// 128-bit loads, double buffered, and are shared by the four waves.
+// 128-bit loads into rings of three tiles, and are shared by the four waves.
 //
-// Per wave and KV tile (scores kept transposed so that no cross-lane movement is needed between
+// Each wave walks its keys in blocks of 32 and software-pipelines three stages, so that the
+// matrix pipe and the vector ALU of its SIMD run side by side (one wave per SIMD: there is no
+// second wave to hide behind): while the VALU does the softmax of block j, the MFMAs issued
+// between its instructions compute S(j+1) = K(j+1) Q^T and O += V(j-1)^T P(j-1).
+//
+// Per wave and key block (scores kept transposed so that no cross-lane movement is needed between
 // the two contractions):
 //   S^T[key, query] = K_tile * Q^T        v_mfma_f32_32x32x16_bf16, A = K from LDS, B = Q in registers
 //   online softmax over keys: each lane owns one query column and 16 keys per 32-key block, the
@@ -18,6 +23,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
+
 
 namespace hydra {
 
@@ -32,6 +40,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 #define HYDRA_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define HYDRA_LDS_BYTE(off) ((__attribute__((address_space(3))) unsigned char*)(uintptr_t)(off))
 #define HYDRA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 constexpr int kWaveTileRows = 64;  // query tokens per wave tile
@@ -52,6 +61,7 @@ struct AttnArgs {
   const int32_t* cu_seqlens;
   const WorkItem* items;
   const int32_t* n_items;
+  int32_t* redo_flags;  // one per work item; set when the item must be recomputed carefully
   int32_t n_q_heads;
   int32_t group;     // n_q_heads / n_kv_heads
   float scale_log2;  // softmax_scale * log2(e)
@@ -64,9 +74,11 @@ struct TileGeom {
   static constexpr int kQkSteps = D / 16;                        // 32x32x16 steps of the QK contraction
   static constexpr int kPvChunks = (D + 31) / 32;                // 32-wide output column blocks of PV
   static constexpr int kTileBytes = kKvTileRows * kRowBytes;     // one K or V tile
-  static constexpr int kStageBytes = 2 * kTileBytes;             // K then V
   static constexpr int kLoadInstr = kTileBytes / 1024;           // wave-wide 16 B/lane loads per tile
-  static constexpr int kLdsBytes = 2 * kStageBytes + 64;         // + slack: D=80 reads V columns 80..95
+  // K tiles and V tiles each live in a ring of kRing LDS tiles; loads run kRing - 2 tiles ahead of use
+  static constexpr int kRing = 4;
+  static constexpr int kPrefetch = kRing - 2;
+  static constexpr int kLdsBytes = 2 * kRing * kTileBytes + 64;  // + slack: D=80 reads V columns 80..95
 };
 
 // XOR swizzles of the 16-byte chunk index inside an LDS row.  Chosen so that the 16 lanes the
@@ -110,38 +122,118 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return r0 + r1;
 }
 
-// Issue this wave's share of the direct-to-LDS loads of one 64-row K tile and V tile.
-// Rows past the end of the sequence re-read the last valid row (always masked later).
+// Everything below uses gfx950-only types and builtins, so the host pass of hipcc only sees the
+// kernel's declaration (it still emits the launch stub).
+#if defined(__HIP_DEVICE_COMPILE__)
+// Loads of one 64-row K or V tile, global -> LDS, 16 bytes per lane, through a buffer resource
+// that covers exactly this sequence's rows of this KV head: rows past the end of the sequence
+// are out of range and arrive as zeros (they are masked later; zeros keep V finite).
+// The per-lane offset is fixed for the whole kernel; the tile advances through the scalar offset.
 template <int D>
-__device__ __forceinline__ void issue_kv_tile_loads(const AttnArgs& a, unsigned char* stage, int wave, int lane, int64_t seq_start,
-                                                    int seq_len, int kv_head, int kv0) {
+struct TileLoader {
   using G = TileGeom<D>;
-  constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
+  static constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t lane_off[kPerWave];  // bytes from the first row of a tile
+  uint32_t row_bytes;           // token stride in bytes
+  int wave;
+
+  template <bool IS_V>
+  __device__ __forceinline__ void init(const uint16_t* base, int64_t stride, int64_t seq_start, int seq_len, int kv_head, int wave_, int lane) {
+    wave = wave_;
+    row_bytes = (uint32_t)(stride * 2);
+    const uint16_t* first = base + seq_start * stride + kv_head * D;
+    const uint32_t bytes = (uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2);
+    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)first, 0, bytes, 0x00020000);
 #pragma unroll
-  for (int u = 0; u < kPerWave; ++u) {
-    const int instr = wave + 4 * u;
-    if (instr < G::kLoadInstr) {
-      const int flat = instr * 64 + lane;
-      const int row = flat / G::kChunks;
-      const int phys = flat % G::kChunks;
-      int tok = kv0 + row;
-      tok = tok < seq_len ? tok : seq_len - 1;
-      const int64_t t = seq_start + tok;
-      const uint16_t* kp = a.k + t * a.k_stride + kv_head * D + k_swizzle<D>(row, phys) * 8;
-      const uint16_t* vp = a.v + t * a.v_stride + kv_head * D + v_swizzle<D>(row, phys) * 8;
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + G::kTileBytes + instr * 1024), 16, 0, 0);
+    for (int u = 0; u < kPerWave; ++u) {
+      const int flat = (wave + 4 * u) * 64 + lane;
+      const int row = flat / G::kChunks, phys = flat % G::kChunks;
+      const int chunk = IS_V ? v_swizzle<D>(row, phys) : k_swizzle<D>(row, phys);
+      lane_off[u] = (uint32_t)row * row_bytes + chunk * 16;
     }
   }
+  // number of load instructions this wave issues per tile
+  __device__ __forceinline__ int per_tile() const {
+    int n = 0;
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) n += (wave + 4 * u < G::kLoadInstr);
+    return n;
+  }
+  __device__ __forceinline__ void issue(unsigned char* dst, int tile) const {
+    const uint32_t soff = (uint32_t)(tile * kKvTileRows) * row_bytes;
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int instr = wave + 4 * u;
+      if (instr < G::kLoadInstr) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HYDRA_LDS_PTR(dst + instr * 1024), 16, lane_off[u], soff, 0, 0);
+    }
+  }
+};
+
+// s_waitcnt vmcnt(n) for a run-time n (the count is an immediate): waits until at most n of this
+// wave's vector-memory loads are still in flight.  Rounds down to a supported value (waits longer).
+__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
+#define HYDRA_VMCNT_CASE(k) \
+  if (n >= k) { asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); return; }
+  HYDRA_VMCNT_CASE(24) HYDRA_VMCNT_CASE(18) HYDRA_VMCNT_CASE(16) HYDRA_VMCNT_CASE(12) HYDRA_VMCNT_CASE(9) HYDRA_VMCNT_CASE(8)
+  HYDRA_VMCNT_CASE(6) HYDRA_VMCNT_CASE(4) HYDRA_VMCNT_CASE(3) HYDRA_VMCNT_CASE(2)
+#undef HYDRA_VMCNT_CASE
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
+
+
+// ---- matrix instructions -------------------------------------------------------------------
+// O += V^T P goes through the compiler's builtin: the accumulators live in accumulation
+// registers, which is where the compiler puts every matrix result of a kernel this large, and it
+// inserts the wait states their readers need.
+// S = K Q^T is written as inline assembly so that its result lands in ordinary registers, where
+// the softmax can read it directly (through the builtin it would arrive in accumulation
+// registers and cost one extra move per score).  The compiler does not see these as matrix
+// instructions, so s_results_to_valu() supplies the wait states between the last of them and
+// the first vector-ALU (or compiler-generated) reader of S; it is issued at the end of every
+// group of QK instructions.  Q is read from accumulation registers.
+typedef __attribute__((ext_vector_type(4))) uint32_t qreg_t;
+
+// O += A(vf) * B(pf)
+__device__ __forceinline__ void mfma_pv(f32x16_t& O, const bf16x8_t& vf, const bf16x8_t& pf) {
+  O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, O, 0, 0, 0);
+}
+// S (+)= A(kf) * B(q)
+__device__ __forceinline__ void mfma_qk(f32x16_t& S, bool first, const bf16x8_t& kf, const qreg_t& q) {
+  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "a"(q));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "a"(q));
+}
+// Move a loaded Q fragment into accumulation registers (tied operand: the compiler emits the copy).
+__device__ __forceinline__ void park_q(qreg_t& home, const qreg_t& loaded) { asm volatile("" : "=a"(home) : "0"(loaded)); }
+// Wait states after the last QK matrix instruction, before anything else touches S.
+__device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(S[0]), "+v"(S[1])); }
+
+#endif  // __HIP_DEVICE_COMPILE__
+
+// Scheduling hints: keep the listed instruction classes in this order inside the current region.
+#define HYDRA_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define HYDRA_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
+#define HYDRA_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+#define HYDRA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+constexpr int kKeyBlock = 32;         // keys per pipeline step
+constexpr int kSlots = 8;             // pipeline slots per key block
+constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_fwd_kernel(const AttnArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
   using G = TileGeom<D>;
   constexpr int KS = G::kQkSteps;
   constexpr int CC = G::kPvChunks;
   constexpr int ROWB = G::kRowBytes;
+  constexpr int NQ = KS;      // QK work units per key block: step s = one K fragment read + 2 MFMAs (qs = 0, 1)
+  constexpr int NP = 2 * CC;  // PV work units per key block: (s2, cc) = one V^T fragment + 2 MFMAs
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
+  // LDS: K ring then V ring; tile t of either lives in ring slot t % kRing.
+  constexpr int R = G::kRing, PD = G::kPrefetch;
+  unsigned char* const k_ring = smem;
+  unsigned char* const v_ring = smem + R * G::kTileBytes;
 
   const int item_idx = blockIdx.x;
   if (item_idx >= *a.n_items) return;
@@ -164,14 +256,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int head = kv_head * a.group + (f - tok_tile * a.group);
   const int q0 = tok_tile * kWaveTileRows;
   const int f_last = (f0 + kWavesPerItem - 1 < n_wave_tiles ? f0 + kWavesPerItem - 1 : n_wave_tiles - 1);
-  const int tiles_wg = CAUSAL ? f_last / a.group + 1 : n_tok_tiles;
-  const int tiles_wave = active ? (CAUSAL ? tok_tile + 1 : n_tok_tiles) : 0;
+  const int W = CAUSAL ? f_last / a.group + 1 : n_tok_tiles;  // KV tiles the workgroup streams
+  // key blocks this wave consumes: keys [0, kv_end)
+  const int kv_end = CAUSAL ? (q0 + kWaveTileRows < seq_len ? q0 + kWaveTileRows : seq_len) : seq_len;
+  const int NB = active ? (kv_end + kKeyBlock - 1) / kKeyBlock : 0;
 
-  // first K/V tile in flight before anything else
-  issue_kv_tile_loads<D>(a, smem, wave, lane, seq_start, seq_len, kv_head, 0);
+  // Workgroup iterations: iteration 0 is the prologue (needs K(0)); iteration t >= 1 needs K tile t
+  // and V tile t - 1 and runs, per wave, key-block steps 2t - 1 and 2t.  There are W + 1 of them.
+  // Load order of the whole item: K(0) V(0) K(1) V(1) ... (K(n) is tile load 2n, V(n) is 2n + 1),
+  // issued PD iterations ahead of use.  Loads complete in order, so "tile X has landed" is
+  // "at most (tiles issued after X) * per_tile of this wave's loads are still in flight".
+  TileLoader<D> k_loader, v_loader;
+  k_loader.template init<false>(a.k, a.k_stride, seq_start, seq_len, kv_head, wave, lane);
+  v_loader.template init<true>(a.v, a.v_stride, seq_start, seq_len, kv_head, wave, lane);
+  const int per_tile = k_loader.per_tile();
+  // after the issue of iteration t, tile loads 0 .. 2(t+PD) are out; iteration t needs 0 .. 2t
+  auto issue_loads = [&](int t) {
+    if (t - 1 + PD < W) v_loader.issue(v_ring + ((t - 1 + PD) % R) * G::kTileBytes, t - 1 + PD);
+    if (t + PD < W) k_loader.issue(k_ring + ((t + PD) % R) * G::kTileBytes, t + PD);
+  };
+  auto wait_for_iteration = [&](int t_next, int t_issued) {
+    const int issued = 2 * (t_issued + PD) + 1 < 2 * W ? 2 * (t_issued + PD) + 1 : 2 * W;
+    const int needed = 2 * t_next + 1 < 2 * W ? 2 * t_next + 1 : 2 * W;
+    wait_vmcnt_at_most((issued - needed) * per_tile);
+  };
+  k_loader.issue(k_ring, 0);
 
-  // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7
-  bf16x8_t qf[2][KS];
+  // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
+  // parked in accumulation registers.
+  qreg_t qf[2][KS];
   int q_lim[2];  // largest visible key index for this lane's query of sub-tile qs
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
@@ -180,21 +293,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     q_lim[qs] = CAUSAL ? row : seq_len - 1;
     const uint16_t* qp = a.q + (seq_start + row) * a.q_stride + head * D + hf * (D / 2);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[qs][s] = *reinterpret_cast<const bf16x8_t*>(qp + 8 * s);
+    for (int s = 0; s < KS; ++s) park_q(qf[qs][s], *reinterpret_cast<const qreg_t*>(qp + 8 * s));
   }
 
-  // LDS read offsets inside a stage
-  uint32_t k_off[KS], v_off[CC];
+  // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
 #pragma unroll
-  for (int s = 0; s < KS; ++s) k_off[s] = m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;
+  for (int n = 0; n < PD; ++n) {
+    if (n < W) v_loader.issue(v_ring + n * G::kTileBytes, n);
+    if (n + 1 < W) k_loader.issue(k_ring + (n + 1) * G::kTileBytes, n + 1);
+  }
+
+  // LDS read addresses: lane part + ring slot of the iteration's K tile / V tile; the key block
+  // inside the tile and the step are immediates.  Advanced once per iteration.
+  uint32_t k_addr[KS], v_addr[CC];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)HYDRA_LDS_PTR(smem);
+#pragma unroll
+  for (int s = 0; s < KS; ++s) k_addr[s] = lds_base + m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;  // K tile 0
   {
     const int r = 4 * hf + (sl >> 2);
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc) {
       const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
-      v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
+      // V tile "-1": the first advance brings it to tile 0
+      v_addr[cc] = lds_base + (R - 1) * G::kTileBytes + R * G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
     }
   }
+  auto advance_addresses = [&](int t) {  // to K tile t, V tile t - 1
+    const int dk = (t % R == 0) ? -(R - 1) * G::kTileBytes : G::kTileBytes;
+    const int dv = ((t - 1) % R == 0) ? -(R - 1) * G::kTileBytes : G::kTileBytes;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) k_addr[s] += dk;
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc) v_addr[cc] += dv;
+  };
 
   f32x16_t o_acc[2][CC];
 #pragma unroll
@@ -203,141 +334,255 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] = 0.f;
-  float row_max[2] = {-3.0e38f, -3.0e38f};
-  float row_sum[2] = {0.f, 0.f};
+  // Softmax reference: the row maximum over key block 0, kept for the whole row.  Exponentials are
+  // taken relative to it, so O never has to be rescaled inside the loop; that is exact as long as
+  // no later score exceeds the reference by more than kMaxLeadLog2 powers of two (far beyond what
+  // bf16 activations produce).  A wave that sees a larger lead flags its work item, and the
+  // flagged items are recomputed afterwards by the careful kernel, which rescales at every tile.
+  float ref_c[2] = {0.f, 0.f};    // reference * c
+  float lead[2];                  // this lane's largest raw score so far (blocks >= 1)
+  float row_sum[2] = {0.f, 0.f};  // this lane's half of the row sum
   const float c = a.scale_log2;
 
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  // LDS fragment reads; rb = key block inside the tile the address registers point at.
+  auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
+    return *reinterpret_cast<const bf16x8_t*>(HYDRA_LDS_BYTE(k_addr[s] + rb * kKeyBlock * ROWB));
+  };
+  // PV unit u = (s2, cc): the V^T fragment of 16 keys x 32 columns
+  auto load_v_frag = [&](int rb, int u) -> bf16x8_t {
+    const int cc = u % CC, s2 = u / CC;
+    const uint32_t at = v_addr[cc] + rb * kKeyBlock * ROWB + s2 * 16 * ROWB;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_BYTE(at));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_BYTE(at + 8 * ROWB));
+    typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
+  };
 
-  for (int t = 0; t < tiles_wg; ++t) {
-    unsigned char* stage = smem + (t & 1) * G::kStageBytes;
-    if (t + 1 < tiles_wg)
-      issue_kv_tile_loads<D>(a, smem + ((t + 1) & 1) * G::kStageBytes, wave, lane, seq_start, seq_len, kv_head, (t + 1) * kKvTileRows);
-
-    if (t < tiles_wave) {
-      const int kv0 = t * kKvTileRows;
-      // ---- S^T = K Q^T ----
-      f32x16_t s_acc[2][2];  // [rb][qs]
+  // Mask of key block j (only blocks that reach past a query's limit need it).
+  auto apply_mask = [&](int j, f32x16_t(&S)[2]) {
+    const int key0 = j * kKeyBlock;
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+    for (int r = 0; r < 16; ++r) {
+      const int key = key0 + 8 * (r >> 2) + 4 * hf + (r & 3);
 #pragma unroll
-        for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
-#pragma unroll
-          for (int qs = 0; qs < 2; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
-        }
-      }
-      // ---- mask (diagonal and tail tiles only) ----
-      const int min_lim = CAUSAL ? q0 : seq_len - 1;
-      const bool need_mask = kv0 + kKvTileRows - 1 > min_lim;
-      if (need_mask) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-#pragma unroll
-            for (int qs = 0; qs < 2; ++qs)
-              if (key > q_lim[qs]) s_acc[rb][qs][r] = -__builtin_inff();
-          }
-      }
-      // ---- online softmax, P in bf16 ----
-      bf16x8_t p_frag[2][2][2];  // [qs][rb][s2]
-#pragma unroll
-      for (int qs = 0; qs < 2; ++qs) {
-        float tmax = s_acc[0][qs][0];
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[rb][qs][r]);
-        tmax = max_with_other_half(tmax);
-        const float m_new = fmaxf(row_max[qs], tmax);
-        const float alpha = fast_exp2((row_max[qs] - m_new) * c);
-        row_max[qs] = m_new;
-        const float mc = m_new * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s_acc[rb][qs][r], c, -mc));
-          if (need_mask) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-              if (key > q_lim[qs]) p[r] = 0.f;
-            }
-          }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) psum += p[r];
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-              f32x2_t pr = {p[8 * s2 + e], p[8 * s2 + e + 1]};
-              bf16x2_t pb = __builtin_convertvector(pr, bf16x2_t);
-              p_frag[qs][rb][s2][e] = pb[0];
-              p_frag[qs][rb][s2][e + 1] = pb[1];
-            }
-        }
-        row_sum[qs] = row_sum[qs] * alpha + psum;
-#pragma unroll
-        for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] *= alpha;
-      }
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const unsigned char* vp = stage + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
-            const s16x4_t hi =
-                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
-            typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-            const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, both);
-#pragma unroll
-            for (int qs = 0; qs < 2; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
-          }
+      for (int qs = 0; qs < 2; ++qs)
+        if (key > q_lim[qs]) S[qs][r] = -__builtin_inff();
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  const int min_lim = CAUSAL ? q0 : seq_len - 1;
+  auto needs_mask = [&](int j) { return j * kKeyBlock + kKeyBlock - 1 > min_lim; };
+
+  // softmax of one element e (0..31: sub-tile e / 16, register e % 16) of a key block
+  auto softmax_element = [&](int e, const f32x16_t(&Sc)[2], bf16x8_t(&Pc)[2][2], const float(&mc)[2], float(&psum)[2], float(&hold)[2])
+                             __attribute__((always_inline)) {
+    const int qs = e / 16, r = e % 16;
+    const float pv = fast_exp2(__builtin_fmaf(Sc[qs][r], c, -mc[qs]));
+    psum[qs] += pv;
+    if ((r & 1) == 0) {
+      hold[qs] = pv;
+    } else {
+      f32x2_t pr = {hold[qs], pv};
+      uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
+      asm volatile("" : "+v"(packed));  // keeps this element's work where it is written
+      const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
+      Pc[qs][r / 8][(r % 8) - 1] = pk[0];
+      Pc[qs][r / 8][r % 8] = pk[1];
+    }
+  };
+
+  // One pipeline step for key block j >= 1 of this wave.  KRB / VRB: key block of K(j+1) and of
+  // V(j-1) inside the tiles the address registers point at.
+  //   VALU : softmax of S(j) (in Sc) -> P(j) (into Pc)
+  //   MFMA : O += V(j-1)^T P(j-1) (P in Pp) and S(j+1) = K(j+1) Q^T (into Sn)
+  // One matrix instruction, then the share of vector work that fits in its shadow, and so on:
+  // the wave issues in order, so this is what lets the two pipes run side by side.
+  constexpr int NM = 2 * (NQ + NP);  // matrix instructions per step
+  constexpr int NV = 34;             // vector work pieces per step: 2 for the lead check, 32 elements
+  auto block_step = [&](auto rb_tag, int j, f32x16_t(&Sc)[2], f32x16_t(&Sn)[2], const bf16x8_t(&Pp)[2][2], bf16x8_t(&Pc)[2][2])
+                        __attribute__((always_inline)) {
+    constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
+    if (needs_mask(j)) apply_mask(j, Sc);
+    float psum[2] = {0.f, 0.f}, hold[2];
+    // vector work piece i of this step: 2 pieces track the largest score seen, 32 are softmax elements
+    auto valu_piece = [&](int i) __attribute__((always_inline)) {
+      if (i < 2) {
+        float t = lead[i];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(t) : "v"(Sc[i][r]), "v"(Sc[i][r + 1]));
+        lead[i] = t;
+      } else {
+        softmax_element(i - 2, Sc, Pc, ref_c, psum, hold);
+      }
+    };
+    // fragments one unit ahead
+    bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt;
+    vf_cur = load_v_frag(RB, 0);
+    kf_cur = load_k_frag(RB, 0);
+    int ms = 0;  // matrix-instruction index inside the step
+    auto shadow = [&](int ms_done) __attribute__((always_inline)) {
+      // vector pieces [ms*NV/NM, (ms+1)*NV/NM) run behind matrix instruction ms
+#pragma unroll
+      for (int i = ms_done * NV / NM; i < (ms_done + 1) * NV / NM; ++i) valu_piece(i);
+      HYDRA_SCHED_FENCE();
+    };
+    constexpr int NU = NQ > NP ? NQ : NP;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      if (u < NP) {
+        if (u + 1 < NP) vf_nxt = load_v_frag(RB, u + 1);
+        const int cc = u % CC, s2 = u / CC;
+        mfma_pv(o_acc[0][cc], vf_cur, Pp[0][s2]);
+        shadow(ms++);
+        mfma_pv(o_acc[1][cc], vf_cur, Pp[1][s2]);
+        shadow(ms++);
+        vf_cur = vf_nxt;
+      }
+      if (u < NQ) {
+        if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
+        mfma_qk(Sn[0], u == 0, kf_cur, qf[0][u]);
+        shadow(ms++);
+        mfma_qk(Sn[1], u == 0, kf_cur, qf[1][u]);
+        shadow(ms++);
+        kf_cur = kf_nxt;
+      }
+    }
+    s_results_to_valu(Sn);
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      row_sum[qs] += psum[qs];
+      asm volatile("" : "+v"(row_sum[qs]));
+    }
+  };
+
+  // PV only (after this wave's last softmax): O += V^T P for key block rb of the V tile in reach
+  auto pv_only = [&](int rb, const bf16x8_t(&Pp)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < NP; ++u) {
+      const bf16x8_t vf = load_v_frag(rb, u);
+      mfma_pv(o_acc[0][u % CC], vf, Pp[0][u / CC]);
+      mfma_pv(o_acc[1][u % CC], vf, Pp[1][u / CC]);
+    }
+  };
+
+  f32x16_t s_a[2], s_b[2];        // S of even / odd key blocks
+  bf16x8_t p_a[2][2], p_b[2][2];  // P of even / odd key blocks
+  using RB0 = std::integral_constant<int, 0>;
+  using RB1 = std::integral_constant<int, 1>;
+
+  {
+    const int issued = 2 * PD + 1 < 2 * W ? 2 * PD + 1 : 2 * W;
+    wait_vmcnt_at_most((issued - 1) * per_tile);  // K(0) and Q have landed
     __syncthreads();
   }
 
+  // iteration 0 (not overlapped): S(0) = K(0) Q^T, softmax of block 0, S(1) = K(1) Q^T
+  if (NB > 0) {
+#pragma unroll
+    for (int s = 0; s < NQ; ++s) {
+      const bf16x8_t kf = load_k_frag(0, s);
+      mfma_qk(s_a[0], s == 0, kf, qf[0][s]);
+      mfma_qk(s_a[1], s == 0, kf, qf[1][s]);
+    }
+    s_results_to_valu(s_a);
+    if (needs_mask(0)) apply_mask(0, s_a);
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      float t = fmaxf(s_a[qs][0], s_a[qs][1]);
+#pragma unroll
+      for (int r = 2; r < 16; ++r) t = fmaxf(t, s_a[qs][r]);
+      t = max_with_other_half(t);
+      ref_c[qs] = t * c;
+      lead[qs] = t;
+    }
+    {
+      float hold[2];
+#pragma unroll
+      for (int e = 0; e < 32; ++e) softmax_element(e, s_a, p_a, ref_c, row_sum, hold);
+    }
+#pragma unroll
+    for (int s = 0; s < NQ; ++s) {  // (computed even when NB == 1: harmless, never read)
+      const bf16x8_t kf = load_k_frag(1, s);
+      mfma_qk(s_b[0], s == 0, kf, qf[0][s]);
+      mfma_qk(s_b[1], s == 0, kf, qf[1][s]);
+    }
+    s_results_to_valu(s_b);
+  }
+  wait_for_iteration(1, 0);
+  __syncthreads();
+
+  // Per wave: steps 1 .. NB-1.  Iterations 1 .. F run two steps each (the hot loop), iteration
+  // F + 1 runs the odd step left over (if any) and the last P V product, later iterations only
+  // keep the workgroup's loads and barriers going.
+  const int F = NB > 0 ? (NB - 1) / 2 : 0;
+  int t = 1;
+  for (; t <= F; ++t) {
+    issue_loads(t);
+    advance_addresses(t);
+    block_step(RB0{}, 2 * t - 1, s_b, s_a, p_a, p_b);
+    block_step(RB1{}, 2 * t, s_a, s_b, p_b, p_a);
+    wait_for_iteration(t + 1, t);
+    __syncthreads();
+  }
+  if (NB > 0 && t <= W) {
+    issue_loads(t);
+    advance_addresses(t);
+    if ((NB - 1) & 1) {
+      block_step(RB0{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
+      pv_only(1, p_b);                               // V block NB - 1 = 2t - 1: second block of V tile t - 1
+    } else {
+      pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
+    }
+    wait_for_iteration(t + 1, t);
+    __syncthreads();
+    ++t;
+  }
+  for (; t <= W; ++t) {
+    issue_loads(t);
+    wait_for_iteration(t + 1, t);
+    __syncthreads();
+  }
+  // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
+  if (NB > 0) {
+    const bool too_far = (lead[0] * c - ref_c[0] > kMaxLeadLog2) || (lead[1] * c - ref_c[1] > kMaxLeadLog2);
+    if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) a.redo_flags[item_idx] = 1;
+  }
   if (!active) return;
-  // ---- epilogue: normalise, round to bf16, store ----
+  // ---- epilogue: normalise, round to bf16, exchange halves so every lane stores 16 bytes ----
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     const float total = sum_with_other_half(row_sum[qs]);
     const float inv = 1.0f / total;
     const int row = q0 + 32 * qs + m;
-    if (row < seq_len) {
-      uint16_t* op = a.out + ((seq_start + row) * a.n_q_heads + head) * D;
+    uint16_t* op = a.out + ((seq_start + (row < seq_len ? row : 0)) * a.n_q_heads + head) * D;
 #pragma unroll
-      for (int cc = 0; cc < CC; ++cc)
+    for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const int col = 32 * cc + 8 * g4 + 4 * hf;
-          if (col < D) {
-            f32x2_t a0 = {o_acc[qs][cc][4 * g4] * inv, o_acc[qs][cc][4 * g4 + 1] * inv};
-            f32x2_t a1 = {o_acc[qs][cc][4 * g4 + 2] * inv, o_acc[qs][cc][4 * g4 + 3] * inv};
-            const bf16x2_t b0 = __builtin_convertvector(a0, bf16x2_t);
-            const bf16x2_t b1 = __builtin_convertvector(a1, bf16x2_t);
-            u32x2_t pk = {__builtin_bit_cast(uint32_t, b0), __builtin_bit_cast(uint32_t, b1)};
-            *reinterpret_cast<u32x2_t*>(op + col) = pk;
+      for (int pair = 0; pair < 2; ++pair) {
+        // register groups g4 = 2*pair and 2*pair+1 hold columns 32cc + 8*g4 + 4*hf + 0..3
+        uint32_t w[2][2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int r = 4 * (2 * pair + k) + 2 * j;
+            f32x2_t x = {o_acc[qs][cc][r] * inv, o_acc[qs][cc][r + 1] * inv};
+            w[k][j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2_t));
           }
+        // low half gives its second group and receives the high half's first group:
+        // afterwards a low lane holds columns 8*(2*pair)+0..7, a high lane 8*(2*pair+1)+0..7
+#pragma unroll
+        for (int j = 0; j < 2; ++j) asm volatile("s_nop 3\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 3" : "+v"(w[0][j]), "+v"(w[1][j]));
+        const int col = 32 * cc + 8 * (2 * pair + hf);
+        if (row < seq_len && col < D) {
+          u32x4_t pk = {w[0][0], w[0][1], w[1][0], w[1][1]};
+          *reinterpret_cast<u32x4_t*>(op + col) = pk;
         }
-    }
+      }
   }
+#else
+  (void)a;
+#endif
 }
 
 }  // namespace hydra

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/hydra_attn.h"
+#include "attn_careful.hpp"
 #include "attn_fwd.hpp"
 #include "kv_write.hpp"
 #include "worklist.hpp"
@@ -15,12 +16,18 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 bool head_dim_supported(int d) { return d == 64 || d == 80 || d == 128; }
 
+// The fast kernel over the whole work list, then the careful kernel over whatever it flagged
+// (normally nothing: a few workgroups read the flags and leave).
 template <int D>
 hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned grid, hipStream_t stream) {
-  if (causal)
+  const unsigned careful_grid = grid < 256u ? grid : 256u;
+  if (causal) {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
-  else
+    hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, true>), dim3(careful_grid), dim3(256), 0, stream, args);
+  } else {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, false>), dim3(grid), dim3(256), 0, stream, args);
+    hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, false>), dim3(careful_grid), dim3(256), 0, stream, args);
+  }
   return hipGetLastError();
 }
 
@@ -56,7 +63,8 @@ int check_attn_sizes(int32_t batch, int32_t total_tokens, int32_t max_seqlen, in
   if (n_q_heads % n_kv_heads != 0) return HYDRA_ERR_INVALID_ARG;
   if (!head_dim_supported(head_dim)) return HYDRA_ERR_UNSUPPORTED;
   if (batch > 0 && total_tokens > 0 && max_seqlen < 1) return HYDRA_ERR_INVALID_ARG;
-  // 32-bit index arithmetic inside the prepass
+  // 32-bit byte offsets inside one sequence's K/V rows (buffer addressing in the attention kernel)
+  // are checked by the callers that know the strides; 32-bit index arithmetic inside the prepass:
   if ((int64_t)n_q_heads * ((int64_t)total_tokens / hydra::kWaveTileRows + batch) > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
   return HYDRA_OK;
 }
@@ -85,17 +93,17 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
   const int group = n_q_heads / n_kv_heads;
   if (causal)
     hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, n_items, item_offset, items, (int)lay.capacity);
+                       group, n_items, item_offset, items, reinterpret_cast<int32_t*>(ws + lay.flags_at), (int)lay.capacity);
   else
     hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, n_items, item_offset, items, (int)lay.capacity);
+                       group, n_items, item_offset, items, reinterpret_cast<int32_t*>(ws + lay.flags_at), (int)lay.capacity);
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride,
                                    int64_t k_token_stride, int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch,
                                    int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                   int32_t causal, float softmax_scale, const void* workspace, size_t workspace_bytes, void* stream) {
+                                   int32_t causal, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
   if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
   if (batch == 0 || total_tokens == 0) return HYDRA_OK;
@@ -105,10 +113,15 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
       v_token_stride < (int64_t)n_kv_heads * head_dim)
     return HYDRA_ERR_INVALID_ARG;
   if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
+  {
+    // the kernel addresses one sequence's K (or V) rows with 32-bit byte offsets
+    const int64_t widest = k_token_stride > v_token_stride ? k_token_stride : v_token_stride;
+    if (((int64_t)max_seqlen + 2 * hydra::kKvTileRows) * widest * 2 >= ((int64_t)1 << 31)) return HYDRA_ERR_UNSUPPORTED;
+  }
   const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
   if (int rc = check_workspace(workspace, workspace_bytes, lay)) return rc;
 
-  const unsigned char* ws = static_cast<const unsigned char*>(workspace);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
   hydra::AttnArgs args;
   args.q = static_cast<const uint16_t*>(q);
   args.k = static_cast<const uint16_t*>(k);
@@ -120,6 +133,7 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   args.cu_seqlens = cu_seqlens;
   args.items = reinterpret_cast<const hydra::WorkItem*>(ws + lay.items_at);
   args.n_items = reinterpret_cast<const int32_t*>(ws);
+  args.redo_flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   args.n_q_heads = n_q_heads;
   args.group = n_q_heads / n_kv_heads;
   // A scale of exactly 0 is replaced by a vanishing positive one: every visible key still gets

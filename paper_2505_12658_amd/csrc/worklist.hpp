@@ -23,9 +23,12 @@ constexpr int kPrepassThreads = 1024;
 //   [0]            n_items
 //   [4 .. 4+B]     item_offset[b]  exclusive prefix of items per sequence (per KV head), B+1 entries
 //   then, 16-byte aligned, WorkItem[capacity]
+//   then int32 redo_flags[capacity]: all zero between calls; the fast attention kernel sets the
+//   flag of an item it cannot finish exactly, the careful kernel redoes the item and clears it
 struct WorkspaceLayout {
   size_t offsets_at;  // bytes
   size_t items_at;    // bytes
+  size_t flags_at;    // bytes
   size_t capacity;    // items
   size_t total;       // bytes
 };
@@ -43,7 +46,8 @@ inline WorkspaceLayout workspace_layout(int64_t batch, int64_t total_tokens, int
   size_t end = w.offsets_at + (size_t)(batch + 1) * 4;
   w.items_at = (end + 15) & ~(size_t)15;
   w.capacity = item_capacity(batch, total_tokens, n_q_heads, n_kv_heads);
-  w.total = w.items_at + w.capacity * sizeof(WorkItem);
+  w.flags_at = w.items_at + w.capacity * sizeof(WorkItem);
+  w.total = w.flags_at + w.capacity * sizeof(int32_t);
   return w;
 }
 
@@ -55,11 +59,12 @@ __device__ __forceinline__ int items_of_sequence(int len, int group) {
 template <bool CAUSAL>
 __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch, int n_kv_heads, int group,
                                                                          int32_t* __restrict__ n_items_out, int32_t* __restrict__ item_offset,
-                                                                         WorkItem* __restrict__ items, int capacity) {
+                                                                         WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags, int capacity) {
   __shared__ int partial[kPrepassThreads];
   __shared__ int hist[kCostBuckets];
   __shared__ int cursor[kCostBuckets];
   const int tid = threadIdx.x;
+  for (int i = tid; i < capacity; i += kPrepassThreads) redo_flags[i] = 0;
 
   // 1. items per sequence -> exclusive prefix (each thread owns a contiguous run of sequences)
   const int per_thread = (batch + kPrepassThreads - 1) / kPrepassThreads;
