@@ -126,14 +126,21 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // kernel's declaration (it still emits the launch stub).
 #if defined(__HIP_DEVICE_COMPILE__)
 // Loads of one 64-row K or V tile, global -> LDS, 16 bytes per lane, through a buffer resource
-// that covers exactly this sequence's rows of this KV head: rows past the end of the sequence
-// are out of range and arrive as zeros (they are masked later; zeros keep V finite).
-// The per-lane offset is fixed for the whole kernel; the tile advances through the scalar offset.
+// that covers exactly the rows of this sequence and KV head from the tile's first row on: rows
+// past the end of the sequence are out of range and arrive as zeros (they are masked later;
+// zeros keep V finite).  The per-lane offset is fixed for the whole kernel; the tile advances
+// through the descriptor's base address.
+//
+// The load is issued from inline assembly on purpose: when the compiler knows that vector-memory
+// loads write LDS, it makes every later LDS read wait for ALL outstanding loads (vmcnt 0), which
+// would serialise the prefetch ring with the compute.  Completion is tracked by hand instead
+// (wait_vmcnt_at_most + the workgroup barrier before a tile's first reader).
 template <int D>
 struct TileLoader {
   using G = TileGeom<D>;
   static constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
-  __amdgpu_buffer_rsrc_t rsrc;
+  uint64_t first_row;           // address of row 0 of this sequence / KV head
+  uint32_t total_bytes;         // bytes from first_row to the end of the last valid row
   uint32_t lane_off[kPerWave];  // bytes from the first row of a tile
   uint32_t row_bytes;           // token stride in bytes
   int wave;
@@ -142,9 +149,8 @@ struct TileLoader {
   __device__ __forceinline__ void init(const uint16_t* base, int64_t stride, int64_t seq_start, int seq_len, int kv_head, int wave_, int lane) {
     wave = wave_;
     row_bytes = (uint32_t)(stride * 2);
-    const uint16_t* first = base + seq_start * stride + kv_head * D;
-    const uint32_t bytes = (uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2);
-    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)first, 0, bytes, 0x00020000);
+    first_row = (uint64_t)(uintptr_t)(base + seq_start * stride + kv_head * D);
+    total_bytes = (uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2);
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const int flat = (wave + 4 * u) * 64 + lane;
@@ -160,12 +166,24 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) n += (wave + 4 * u < G::kLoadInstr);
     return n;
   }
-  __device__ __forceinline__ void issue(unsigned char* dst, int tile) const {
-    const uint32_t soff = (uint32_t)(tile * kKvTileRows) * row_bytes;
+  // lds_dst: LDS byte address of the tile's ring slot
+  __device__ __forceinline__ void issue(uint32_t lds_dst, int tile) const {
+    const uint32_t skip = (uint32_t)(tile * kKvTileRows) * row_bytes;
+    const uint64_t base = first_row + skip;
+    const uint32_t left = total_bytes > skip ? total_bytes - skip : 0u;
+    u32x4_t rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    rsrc[2] = __builtin_amdgcn_readfirstlane(left);
+    rsrc[3] = 0x00020000u;
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const int instr = wave + 4 * u;
-      if (instr < G::kLoadInstr) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HYDRA_LDS_PTR(dst + instr * 1024), 16, lane_off[u], soff, 0, 0);
+      if (instr < G::kLoadInstr) {
+        // (m0 is reserved: the compiler only ever sets it immediately before an instruction of its own that reads it)
+        const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + instr * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
+      }
     }
   }
 };
@@ -186,7 +204,7 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n) {
 // O += V^T P goes through the compiler's builtin: the accumulators live in accumulation
 // registers, which is where the compiler puts every matrix result of a kernel this large, and it
 // inserts the wait states their readers need.
-// S = K Q^T is written as inline assembly so that its result lands in ordinary registers, where
+// S = K Q'^T is written as inline assembly so that its result lands in ordinary registers, where
 // the softmax can read it directly (through the builtin it would arrive in accumulation
 // registers and cost one extra move per score).  The compiler does not see these as matrix
 // instructions, so s_results_to_valu() supplies the wait states between the last of them and
@@ -198,10 +216,15 @@ typedef __attribute__((ext_vector_type(4))) uint32_t qreg_t;
 __device__ __forceinline__ void mfma_pv(f32x16_t& O, const bf16x8_t& vf, const bf16x8_t& pf) {
   O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, O, 0, 0, 0);
 }
-// S (+)= A(kf) * B(q)
-__device__ __forceinline__ void mfma_qk(f32x16_t& S, bool first, const bf16x8_t& kf, const qreg_t& q) {
-  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "a"(q));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "a"(q));
+// S = A(kf) * B(q) + init, then S += A(kf) * B(q)
+__device__ __forceinline__ void mfma_qk_zero(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "a"(q));
+}
+__device__ __forceinline__ void mfma_qk_init(f32x16_t& S, const f32x16_t& init, const bf16x8_t& kf, const qreg_t& q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(kf), "a"(q), "v"(init));
+}
+__device__ __forceinline__ void mfma_qk_acc(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "a"(q));
 }
 // Move a loaded Q fragment into accumulation registers (tied operand: the compiler emits the copy).
 __device__ __forceinline__ void park_q(qreg_t& home, const qreg_t& loaded) { asm volatile("" : "=a"(home) : "0"(loaded)); }
@@ -232,8 +255,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
   // LDS: K ring then V ring; tile t of either lives in ring slot t % kRing.
   constexpr int R = G::kRing, PD = G::kPrefetch;
-  unsigned char* const k_ring = smem;
-  unsigned char* const v_ring = smem + R * G::kTileBytes;
+  const uint32_t k_ring = (uint32_t)(uintptr_t)HYDRA_LDS_PTR(smem);  // LDS byte addresses
+  const uint32_t v_ring = k_ring + R * G::kTileBytes;
 
   const int item_idx = blockIdx.x;
   if (item_idx >= *a.n_items) return;
@@ -284,8 +307,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
   // parked in accumulation registers.
+  const float c = a.scale_log2;
   qreg_t qf[2][KS];
   int q_lim[2];  // largest visible key index for this lane's query of sub-tile qs
+  bf16x8_t q_raw[2][KS];
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     int row = q0 + 32 * qs + m;
@@ -293,7 +318,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     q_lim[qs] = CAUSAL ? row : seq_len - 1;
     const uint16_t* qp = a.q + (seq_start + row) * a.q_stride + head * D + hf * (D / 2);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) park_q(qf[qs][s], *reinterpret_cast<const qreg_t*>(qp + 8 * s));
+    for (int s = 0; s < KS; ++s) q_raw[qs][s] = *reinterpret_cast<const bf16x8_t*>(qp + 8 * s);  // all loads first
   }
 
   // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
@@ -303,10 +328,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (n + 1 < W) k_loader.issue(k_ring + (n + 1) * G::kTileBytes, n + 1);
   }
 
+  // Q' = bf16(Q * scale * log2 e): the scores come out of the matrix unit in log2 units, and with the
+  // accumulator started at -reference the softmax needs one v_exp per score.
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      bf16x8_t scaled;
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        f32x2_t f = {(float)q_raw[qs][s][e] * c, (float)q_raw[qs][s][e + 1] * c};
+        const bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+        scaled[e] = b[0];
+        scaled[e + 1] = b[1];
+      }
+      park_q(qf[qs][s], __builtin_bit_cast(qreg_t, scaled));
+    }
+
   // LDS read addresses: lane part + ring slot of the iteration's K tile / V tile; the key block
   // inside the tile and the step are immediates.  Advanced once per iteration.
   uint32_t k_addr[KS], v_addr[CC];
-  const uint32_t lds_base = (uint32_t)(uintptr_t)HYDRA_LDS_PTR(smem);
+  const uint32_t lds_base = k_ring;
 #pragma unroll
   for (int s = 0; s < KS; ++s) k_addr[s] = lds_base + m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;  // K tile 0
   {
@@ -334,15 +376,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] = 0.f;
-  // Softmax reference: the row maximum over key block 0, kept for the whole row.  Exponentials are
-  // taken relative to it, so O never has to be rescaled inside the loop; that is exact as long as
-  // no later score exceeds the reference by more than kMaxLeadLog2 powers of two (far beyond what
-  // bf16 activations produce).  A wave that sees a larger lead flags its work item, and the
-  // flagged items are recomputed afterwards by the careful kernel, which rescales at every tile.
-  float ref_c[2] = {0.f, 0.f};    // reference * c
-  float lead[2];                  // this lane's largest raw score so far (blocks >= 1)
-  float row_sum[2] = {0.f, 0.f};  // this lane's half of the row sum
-  const float c = a.scale_log2;
+  // Softmax reference: the row maximum over key block 0, kept for the whole row.  Every later
+  // score accumulator starts at -reference, so the matrix unit hands back (score - reference) in
+  // log2 units and the exponential needs no further arithmetic; O never has to be rescaled
+  // inside the loop.  That is exact as long as no later score exceeds the reference by more than
+  // kMaxLeadLog2 powers of two (far beyond what bf16 activations produce).  A wave that sees a
+  // larger lead flags its work item, and the flagged items are recomputed afterwards by the
+  // careful kernel, which rescales at every tile.
+  f32x16_t neg_ref[2];                    // -reference, broadcast over the 16 registers of a block
+  float lead[2] = {0.f, 0.f};             // this lane's largest (score - reference) so far
+  float row_sum[2] = {0.f, 0.f};          // this lane's half of the row sum (of the bf16-rounded p)
 
   // LDS fragment reads; rb = key block inside the tile the address registers point at.
   auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
@@ -373,22 +416,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int min_lim = CAUSAL ? q0 : seq_len - 1;
   auto needs_mask = [&](int j) { return j * kKeyBlock + kKeyBlock - 1 > min_lim; };
 
-  // softmax of one element e (0..31: sub-tile e / 16, register e % 16) of a key block
-  auto softmax_element = [&](int e, const f32x16_t(&Sc)[2], bf16x8_t(&Pc)[2][2], const float(&mc)[2], float(&psum)[2], float(&hold)[2])
-                             __attribute__((always_inline)) {
-    const int qs = e / 16, r = e % 16;
-    const float pv = fast_exp2(__builtin_fmaf(Sc[qs][r], c, -mc[qs]));
-    psum[qs] += pv;
-    if ((r & 1) == 0) {
-      hold[qs] = pv;
-    } else {
-      f32x2_t pr = {hold[qs], pv};
-      uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
-      asm volatile("" : "+v"(packed));  // keeps this element's work where it is written
-      const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
-      Pc[qs][r / 8][(r % 8) - 1] = pk[0];
-      Pc[qs][r / 8][r % 8] = pk[1];
-    }
+  // softmax of one pair of elements (pair 0..15: sub-tile pair / 8, registers 2*(pair%8), +1) of a
+  // key block whose S already holds (score - reference): exponentials, rounding to bf16, and the
+  // row sum of the rounded values through a 2-element dot product with (1, 1).
+  auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[2], bf16x8_t(&Pc)[2][2], float(&psum)[2]) __attribute__((always_inline)) {
+    const int qs = pair / 8, r = 2 * (pair % 8);
+    f32x2_t pr = {fast_exp2(Sc[qs][r]), fast_exp2(Sc[qs][r + 1])};
+    bf16x2_t pk = __builtin_convertvector(pr, bf16x2_t);
+    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+    psum[qs] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum[qs], false);
+    asm volatile("" : "+v"(psum[qs]));  // keeps this pair's work where it is written
+    Pc[qs][r / 8][r % 8] = pk[0];
+    Pc[qs][r / 8][r % 8 + 1] = pk[1];
   };
 
   // One pipeline step for key block j >= 1 of this wave.  KRB / VRB: key block of K(j+1) and of
@@ -398,13 +437,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // One matrix instruction, then the share of vector work that fits in its shadow, and so on:
   // the wave issues in order, so this is what lets the two pipes run side by side.
   constexpr int NM = 2 * (NQ + NP);  // matrix instructions per step
-  constexpr int NV = 34;             // vector work pieces per step: 2 for the lead check, 32 elements
+  constexpr int NV = 18;             // vector work pieces per step: 2 for the lead check, 16 element pairs
   auto block_step = [&](auto rb_tag, int j, f32x16_t(&Sc)[2], f32x16_t(&Sn)[2], const bf16x8_t(&Pp)[2][2], bf16x8_t(&Pc)[2][2])
                         __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
     if (needs_mask(j)) apply_mask(j, Sc);
-    float psum[2] = {0.f, 0.f}, hold[2];
-    // vector work piece i of this step: 2 pieces track the largest score seen, 32 are softmax elements
+    float psum[2] = {0.f, 0.f};
+    // vector work piece i of this step: 2 pieces track the largest score seen, 16 are softmax pairs
     auto valu_piece = [&](int i) __attribute__((always_inline)) {
       if (i < 2) {
         float t = lead[i];
@@ -412,7 +451,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int r = 0; r < 16; r += 2) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(t) : "v"(Sc[i][r]), "v"(Sc[i][r + 1]));
         lead[i] = t;
       } else {
-        softmax_element(i - 2, Sc, Pc, ref_c, psum, hold);
+        softmax_pair(i - 2, Sc, Pc, psum);
       }
     };
     // fragments one unit ahead
@@ -427,8 +466,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       HYDRA_SCHED_FENCE();
     };
     constexpr int NU = NQ > NP ? NQ : NP;
+    static_assert(NP >= NQ, "the step must end with PV instructions: they cover the wait states of the last QK result");
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
+      if (u < NQ) {
+        if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
+        if (u == 0) mfma_qk_init(Sn[0], neg_ref[0], kf_cur, qf[0][u]); else mfma_qk_acc(Sn[0], kf_cur, qf[0][u]);
+        shadow(ms++);
+        if (u == 0) mfma_qk_init(Sn[1], neg_ref[1], kf_cur, qf[1][u]); else mfma_qk_acc(Sn[1], kf_cur, qf[1][u]);
+        shadow(ms++);
+        kf_cur = kf_nxt;
+      }
       if (u < NP) {
         if (u + 1 < NP) vf_nxt = load_v_frag(RB, u + 1);
         const int cc = u % CC, s2 = u / CC;
@@ -438,16 +486,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         shadow(ms++);
         vf_cur = vf_nxt;
       }
-      if (u < NQ) {
-        if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
-        mfma_qk(Sn[0], u == 0, kf_cur, qf[0][u]);
-        shadow(ms++);
-        mfma_qk(Sn[1], u == 0, kf_cur, qf[1][u]);
-        shadow(ms++);
-        kf_cur = kf_nxt;
-      }
     }
-    s_results_to_valu(Sn);
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
       row_sum[qs] += psum[qs];
@@ -476,13 +515,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __syncthreads();
   }
 
-  // iteration 0 (not overlapped): S(0) = K(0) Q^T, softmax of block 0, S(1) = K(1) Q^T
+  // iteration 0 (not overlapped): S(0) = K(0) Q'^T, reference = row maximum of block 0, softmax of
+  // block 0, S(1) = K(1) Q'^T - reference
   if (NB > 0) {
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {
       const bf16x8_t kf = load_k_frag(0, s);
-      mfma_qk(s_a[0], s == 0, kf, qf[0][s]);
-      mfma_qk(s_a[1], s == 0, kf, qf[1][s]);
+      if (s == 0) mfma_qk_zero(s_a[0], kf, qf[0][s]); else mfma_qk_acc(s_a[0], kf, qf[0][s]);
+      if (s == 0) mfma_qk_zero(s_a[1], kf, qf[1][s]); else mfma_qk_acc(s_a[1], kf, qf[1][s]);
     }
     s_results_to_valu(s_a);
     if (needs_mask(0)) apply_mask(0, s_a);
@@ -492,19 +532,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int r = 2; r < 16; ++r) t = fmaxf(t, s_a[qs][r]);
       t = max_with_other_half(t);
-      ref_c[qs] = t * c;
-      lead[qs] = t;
-    }
-    {
-      float hold[2];
 #pragma unroll
-      for (int e = 0; e < 32; ++e) softmax_element(e, s_a, p_a, ref_c, row_sum, hold);
+      for (int r = 0; r < 16; ++r) {
+        neg_ref[qs][r] = -t;
+        s_a[qs][r] -= t;
+      }
     }
+#pragma unroll
+    for (int pair = 0; pair < 16; ++pair) softmax_pair(pair, s_a, p_a, row_sum);
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {  // (computed even when NB == 1: harmless, never read)
       const bf16x8_t kf = load_k_frag(1, s);
-      mfma_qk(s_b[0], s == 0, kf, qf[0][s]);
-      mfma_qk(s_b[1], s == 0, kf, qf[1][s]);
+      if (s == 0) mfma_qk_init(s_b[0], neg_ref[0], kf, qf[0][s]); else mfma_qk_acc(s_b[0], kf, qf[0][s]);
+      if (s == 0) mfma_qk_init(s_b[1], neg_ref[1], kf, qf[1][s]); else mfma_qk_acc(s_b[1], kf, qf[1][s]);
     }
     s_results_to_valu(s_b);
   }
@@ -544,7 +584,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
   if (NB > 0) {
-    const bool too_far = (lead[0] * c - ref_c[0] > kMaxLeadLog2) || (lead[1] * c - ref_c[1] > kMaxLeadLog2);
+    const bool too_far = lead[0] > kMaxLeadLog2 || lead[1] > kMaxLeadLog2;
     if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) a.redo_flags[item_idx] = 1;
   }
   if (!active) return;
