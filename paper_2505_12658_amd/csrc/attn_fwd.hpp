@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // careful kernel, which rescales at every tile.
   f32x16_t neg_ref[2];                    // -reference, broadcast over the 16 registers of a block
   float lead[2] = {0.f, 0.f};             // this lane's largest (score - reference) so far
-  float row_sum[2] = {0.f, 0.f};          // this lane's half of the row sum (of the bf16-rounded p)
+  float row_sum[2] = {0.f, 0.f};          // this lane's half of the row sum
 
   // LDS fragment reads; rb = key block inside the tile the address registers point at.
   auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
@@ -417,15 +417,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   auto needs_mask = [&](int j) { return j * kKeyBlock + kKeyBlock - 1 > min_lim; };
 
   // softmax of one pair of elements (pair 0..15: sub-tile pair / 8, registers 2*(pair%8), +1) of a
-  // key block whose S already holds (score - reference): exponentials, rounding to bf16, and the
-  // row sum of the rounded values through a 2-element dot product with (1, 1).
+  // key block whose S already holds (score - reference): exponentials, row sum, rounding to bf16.
+  // (The sum is two plain adds on purpose: the 2-element dot-product instruction would halve them,
+  // but it runs in the matrix pipe and stalls behind the matrix instructions it is meant to hide in.)
   auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[2], bf16x8_t(&Pc)[2][2], float(&psum)[2]) __attribute__((always_inline)) {
     const int qs = pair / 8, r = 2 * (pair % 8);
     f32x2_t pr = {fast_exp2(Sc[qs][r]), fast_exp2(Sc[qs][r + 1])};
-    bf16x2_t pk = __builtin_convertvector(pr, bf16x2_t);
-    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
-    psum[qs] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum[qs], false);
-    asm volatile("" : "+v"(psum[qs]));  // keeps this pair's work where it is written
+    psum[qs] += pr[0];
+    psum[qs] += pr[1];
+    uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
+    asm volatile("" : "+v"(packed), "+v"(psum[qs]));  // keeps this pair's work where it is written
+    const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
     Pc[qs][r / 8][r % 8] = pk[0];
     Pc[qs][r / 8][r % 8 + 1] = pk[1];
   };
