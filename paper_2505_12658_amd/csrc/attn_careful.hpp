@@ -62,9 +62,8 @@ __device__ __forceinline__ void run_item(const AttnArgs& a, const WorkItem item,
   constexpr int KS = G::kQkSteps;
   constexpr int CC = G::kPvChunks;
   constexpr int ROWB = G::kRowBytes;
-  const int seq = item.x, kv_head = item.y, f0 = item.z;
-  const int64_t seq_start = a.cu_seqlens[seq];
-  const int seq_len = a.cu_seqlens[seq + 1] - a.cu_seqlens[seq];
+  const int64_t seq_start = item.x;
+  const int seq_len = item.y, f0 = item.z, kv_head = item.w;
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
 

@@ -47,9 +47,11 @@ constexpr int kWaveTileRows = 64;  // query tokens per wave tile
 constexpr int kKvTileRows = 64;    // keys per LDS tile
 constexpr int kWavesPerItem = 4;   // wave tiles per work-list item
 
-// One work-list entry, written by the device prepass from cu_seqlens.
-//   x = sequence index, y = KV head, z = first flattened wave tile of the item
-//   (flattened index f = token_tile * group + head_in_group), w = number of KV tiles (cost).
+// One work-list entry, written by the device prepass from cu_seqlens; it carries everything the
+// kernel needs, so a workgroup starts its loads after a single dependent read.
+//   x = first packed token of the sequence, y = sequence length (0: empty entry past the end of
+//   the list), z = first flattened wave tile of the item (flattened index f = token_tile * group
+//   + head_in_group), w = KV head.
 typedef int4 WorkItem;
 
 struct AttnArgs {
@@ -259,11 +261,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const uint32_t v_ring = k_ring + R * G::kTileBytes;
 
   const int item_idx = blockIdx.x;
-  if (item_idx >= *a.n_items) return;
   const WorkItem item = a.items[item_idx];
-  const int seq = item.x, kv_head = item.y, f0 = item.z;
-  const int64_t seq_start = a.cu_seqlens[seq];
-  const int seq_len = a.cu_seqlens[seq + 1] - a.cu_seqlens[seq];
+  const int64_t seq_start = item.x;
+  const int seq_len = item.y, f0 = item.z, kv_head = item.w;
+  if (seq_len == 0) return;
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
 

@@ -98,6 +98,9 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   int total = per_head * n_kv_heads;
   if (total > capacity) total = capacity;  // cannot happen for valid cu_seqlens; keeps stores in bounds
   if (tid == 0) *n_items_out = total;
+  // entries past the end of the list are marked empty (length 0): the attention kernel is launched
+  // over the whole capacity and recognises them without reading the item count
+  for (int i = total + tid; i < capacity; i += kPrepassThreads) items[i] = make_int4(0, 0, 0, 0);
 
   // 2. histogram of costs, 3. descending bucket starts, 4. scatter
   for (int pass = 0; pass < 2; ++pass) {
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
         atomicAdd(&hist[bucket], 1);
       } else {
         const int pos = hist[bucket] + atomicAdd(&cursor[bucket], 1);
-        items[pos] = make_int4(b, kv_head, f0, cost);
+        items[pos] = make_int4(cu[b], len, f0, kv_head);
       }
     }
     __syncthreads();
