@@ -25,6 +25,7 @@ import synth_inputs as si  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA, 256 CUs x 4096 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+CALIBRATION_COPY_BYTES = 1 << 30
 HEADLINE = "qwen2vl_7b_prefill"
 OTHERS = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode"]
 
@@ -166,6 +167,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (cold last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain elementwise copy of 1 GiB (fp32 x + 0 -> y): the known-size kernel that "
+                         "hardware-counter readings of FETCH_SIZE / WRITE_SIZE are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (sequences are independent, so more GPUs would each take a "
@@ -222,6 +226,15 @@ def main():
                               "frac": gbs / PEAK_HBM_GBS, "avg_kernel_us": float(kvw_t.mean()) * 1e6, "bytes": w.kv_write_bytes()}
     host_qkv = batch.host_qkv
     del batch
+    if args.calibration_copy:
+        src = torch.ones(CALIBRATION_COPY_BYTES // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        result["calibration_copy"] = {"kernel": "torch elementwise add(x, 0) -> y, fp32", "bytes_read": CALIBRATION_COPY_BYTES,
+                                      "bytes_written": CALIBRATION_COPY_BYTES, "launches": 3}
+        del src, dst
     torch.cuda.empty_cache()
 
     if not args.no_others:

@@ -257,13 +257,18 @@ __device__ __forceinline__ void run_item(const AttnArgs& a, const WorkItem item,
 
 #endif  // __HIP_DEVICE_COMPILE__
 
-// Grid-stride over the work list: every workgroup looks at the flags of its items and redoes the
-// flagged ones, clearing each flag it consumes so that the flags are all zero for the next call.
+// Runs after the fast kernel on the same stream.  It first puts the fast kernel's queue heads back
+// to zero for the next call.  When no item was flagged (the normal case) every workgroup reads one
+// word and leaves.  Otherwise the workgroups grid-stride over the work list and redo the flagged
+// items, clearing each flag they consume; the last workgroup to finish clears the summary word,
+// so that everything is zero again for the next call.
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_fwd_careful_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[StageGeom<D>::kLdsBytes];
-  const int n_items = *a.n_items;
+  if (blockIdx.x == 0 && threadIdx.x < kXcds) a.ctrl->queue_head[threadIdx.x] = 0;
+  if (__hip_atomic_load(&a.ctrl->redo_any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+  const int n_items = a.ctrl->n_items;
   for (int i = blockIdx.x; i < n_items; i += gridDim.x) {
     const int flagged = a.redo_flags[i];
     __syncthreads();
@@ -271,6 +276,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (threadIdx.x == 0) a.redo_flags[i] = 0;
     run_item<D, CAUSAL>(a, a.items[i], smem);
     __syncthreads();
+  }
+  // every workgroup has read the summary word before it counts itself done
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const int done = atomicAdd(&a.ctrl->careful_done, 1);
+    if (done == (int)gridDim.x - 1) {
+      a.ctrl->careful_done = 0;
+      a.ctrl->redo_any = 0;
+    }
   }
 #else
   (void)a;

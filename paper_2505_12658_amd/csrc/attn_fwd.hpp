@@ -3,7 +3,12 @@
 // One workgroup (4 wavefronts, one per SIMD, up to 512 registers each) runs one work-list item:
 // up to four "wave tiles" that share a sequence and a KV head.  A wave tile is 64 consecutive
 // query tokens of one query head.  K/V tiles of 64 keys stream global -> LDS with direct-to-LDS
-// 128-bit loads into rings of three tiles, and are shared by the four waves.
+// 128-bit loads into rings of four tiles, and are shared by the four waves.
+//
+// The kernel is persistent: one workgroup per compute unit, each pulling items from the queue of
+// the accelerator die (XCD) it runs on.  The prepass puts all items of one (sequence, KV head)
+// into the same queue, next to each other, so the workgroups that stream the same K/V rows run on
+// the same die at about the same time and share them through that die's L2.
 //
 // Each wave walks its keys in blocks of 32 and software-pipelines three stages, so that the
 // matrix pipe and the vector ALU of its SIMD run side by side (one wave per SIMD: there is no
@@ -54,6 +59,22 @@ constexpr int kWavesPerItem = 4;   // wave tiles per work-list item
 //   + head_in_group), w = KV head.
 typedef int4 WorkItem;
 
+constexpr int kXcds = 8;  // accelerator dies; workgroup ids are dealt to them round-robin, each die has its own L2
+
+// Control block at the start of the workspace.  The work list is one array; the entries
+// [xcd_start[x], xcd_start[x + 1]) form the queue of die x and queue_head[x] counts how many of
+// them have been claimed in the current attention call.
+struct WorkControl {
+  int32_t n_items;
+  int32_t xcd_start[kXcds + 1];
+  int32_t reserved0[6];
+  int32_t queue_head[kXcds];  // zero between calls
+  int32_t redo_any;           // nonzero when some redo flag is set
+  int32_t careful_done;       // workgroups of the careful kernel that have finished (only counted when redo_any)
+  int32_t reserved1[6];
+};
+static_assert(sizeof(WorkControl) == 128, "control block layout");
+
 struct AttnArgs {
   const uint16_t* q;
   const uint16_t* k;
@@ -62,7 +83,7 @@ struct AttnArgs {
   int64_t q_stride, k_stride, v_stride;  // elements per token
   const int32_t* cu_seqlens;
   const WorkItem* items;
-  const int32_t* n_items;
+  WorkControl* ctrl;
   int32_t* redo_flags;  // one per work item; set when the item must be recomputed carefully
   int32_t n_q_heads;
   int32_t group;     // n_q_heads / n_kv_heads
@@ -241,6 +262,30 @@ __device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volati
 #define HYDRA_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
 #define HYDRA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Claims the next unclaimed entry of the work list for the calling workgroup: first from the queue
+// of its own die, and when that one is empty from the next die's queue that still has entries
+// (which keeps the dies level at the end of the kernel).  Called by all lanes of ONE wave; returns
+// the list index, or -1 when every queue is empty.  Heads only grow, so the loop ends.
+__device__ __forceinline__ int claim_item(WorkControl* ctrl, int xcc, int lane) {
+  int y = xcc;
+  for (;;) {
+    const int begin = ctrl->xcd_start[y], end = ctrl->xcd_start[y + 1];
+    int pos = 0;
+    if (lane == 0) pos = atomicAdd(&ctrl->queue_head[y], 1);
+    pos = __builtin_amdgcn_readfirstlane(pos);
+    if (pos < end - begin) return begin + pos;
+    const int z = (xcc + lane) & (kXcds - 1);
+    bool has = false;
+    if (lane < kXcds) {
+      const int head = __hip_atomic_load(&ctrl->queue_head[z], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      has = head < ctrl->xcd_start[z + 1] - ctrl->xcd_start[z];
+    }
+    const uint64_t avail = __builtin_amdgcn_ballot_w64(has);
+    if (avail == 0) return -1;
+    y = (xcc + (int)__builtin_ctzll(avail)) & (kXcds - 1);
+  }
+}
+
 constexpr int kKeyBlock = 32;         // keys per pipeline step
 constexpr int kSlots = 8;             // pipeline slots per key block
 constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
@@ -260,17 +305,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const uint32_t k_ring = (uint32_t)(uintptr_t)HYDRA_LDS_PTR(smem);  // LDS byte addresses
   const uint32_t v_ring = k_ring + R * G::kTileBytes;
 
-  const int item_idx = blockIdx.x;
-  const WorkItem item = a.items[item_idx];
-  const int64_t seq_start = item.x;
-  const int seq_len = item.y, f0 = item.z, kv_head = item.w;
-  if (seq_len == 0) return;
+  const int lane_id = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // die this workgroup runs on (hardware id register XCC_ID, bits 3:0)
+  const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
+  __shared__ int s_claim[8];
+
+  // Wave 0 claims the items for the whole workgroup, one round ahead: the claim for the next
+  // round is issued at the top of a round, resolved (and the item read) before the hot loop, and
+  // posted in LDS after it, so that none of its latency shows.
+  auto post_claim = [&](int idx) {  // wave 0: read the item and post it for the next round
+    WorkItem it = make_int4(0, 0, 0, 0);
+    if (idx >= 0) it = a.items[idx];
+    if (lane_id == 0) {
+      s_claim[0] = it.x;
+      s_claim[1] = it.y;
+      s_claim[2] = it.z;
+      s_claim[3] = it.w;
+      s_claim[4] = idx;
+    }
+  };
+  const int own_begin = a.ctrl->xcd_start[xcc], own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
+  if (wave == 0) post_claim(claim_item(a.ctrl, xcc, lane_id));
+
+  for (;;) {  // one work item per round
+  __syncthreads();
+  // Everything derived from the lane number is recomputed in every round (the empty statement hides
+  // the value from the optimiser): kept across rounds, dozens of such lane constants would sit in
+  // registers through the hot loop, which has none to spare.
+  int lane = lane_id;
+  asm volatile("" : "+v"(lane));
+  const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
+  const int64_t seq_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
+  const int seq_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
+  const int f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
+  const int kv_head = __builtin_amdgcn_readfirstlane(s_claim[3]);
+  const int item_idx = __builtin_amdgcn_readfirstlane(s_claim[4]);
+  if (seq_len == 0) break;
+  int pending_claim = 0;  // wave 0, lane 0: position claimed in this die's queue for the next round
+  if (wave == 0 && lane == 0) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc], 1);
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
 
   // this wave's tile
   int f = f0 + wave;
@@ -553,6 +628,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   wait_for_iteration(1, 0);
   __syncthreads();
+  int next_idx = -1;
+  WorkItem next_item = make_int4(0, 0, 0, 0);
+  if (wave == 0) {
+    const int pos = __builtin_amdgcn_readfirstlane(pending_claim);
+    // own queue empty: take from another die's queue (only at the very end of the kernel)
+    next_idx = pos < own_count ? own_begin + pos : claim_item(a.ctrl, xcc, lane);
+    if (next_idx >= 0) next_item = a.items[next_idx];  // (uniform address: a scalar load, held in scalar registers)
+  }
 
   // Per wave: steps 1 .. NB-1.  Iterations 1 .. F run two steps each (the hot loop), iteration
   // F + 1 runs the odd step left over (if any) and the last P V product, later iterations only
@@ -573,6 +656,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if ((NB - 1) & 1) {
       block_step(RB0{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
       pv_only(1, p_b);                               // V block NB - 1 = 2t - 1: second block of V tile t - 1
+      // The step above also produced S(NB) into s_a, which nobody reads.  Its registers must still
+      // stay reserved until those matrix instructions have retired: the compiler takes an assembly
+      // statement's outputs as written the moment it issues, and would otherwise hand the registers
+      // to other values that the late write-back then overwrites.
+      asm volatile("" : : "v"(s_a[0]), "v"(s_a[1]));
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
     }
@@ -585,13 +673,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     wait_for_iteration(t + 1, t);
     __syncthreads();
   }
+  // every wave has read this round's claim long ago (there has been at least one barrier since)
+  if (wave == 0 && lane == 0) {
+    s_claim[0] = next_item.x;
+    s_claim[1] = next_item.y;
+    s_claim[2] = next_item.z;
+    s_claim[3] = next_item.w;
+    s_claim[4] = next_idx;
+  }
   // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
   if (NB > 0) {
     const bool too_far = lead[0] > kMaxLeadLog2 || lead[1] > kMaxLeadLog2;
-    if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) a.redo_flags[item_idx] = 1;
+    if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) {
+      a.redo_flags[item_idx] = 1;
+      a.ctrl->redo_any = 1;
+    }
   }
-  if (!active) return;
   // ---- epilogue: normalise, round to bf16, exchange halves so every lane stores 16 bytes ----
+  if (active) {
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     const float total = sum_with_other_half(row_sum[qs]);
@@ -623,6 +722,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
   }
+  }
+  }  // next work item
 #else
   (void)a;
 #endif

@@ -16,11 +16,20 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 bool head_dim_supported(int d) { return d == 64 || d == 80 || d == 128; }
 
+// Compute units of the current device (0 if the runtime cannot tell).  Looked up on every call:
+// the library keeps no state, and the attribute query does not touch the device.
+unsigned compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+  return (unsigned)n;
+}
+
 // The fast kernel over the whole work list, then the careful kernel over whatever it flagged
 // (normally nothing: a few workgroups read the flags and leave).
 template <int D>
 hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned grid, hipStream_t stream) {
-  const unsigned careful_grid = grid < 256u ? grid : 256u;
+  const unsigned careful_grid = grid;
   if (causal) {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
     hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, true>), dim3(careful_grid), dim3(256), 0, stream, args);
@@ -87,16 +96,18 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  int32_t* n_items = reinterpret_cast<int32_t*>(ws);
-  int32_t* item_offset = reinterpret_cast<int32_t*>(ws + lay.offsets_at);
+  hydra::WorkControl* ctrl = reinterpret_cast<hydra::WorkControl*>(ws);
+  int32_t* sorted_seq = reinterpret_cast<int32_t*>(ws + lay.sorted_at);
+  int32_t* queue_prefix = reinterpret_cast<int32_t*>(ws + lay.prefix_at);
   hydra::WorkItem* items = reinterpret_cast<hydra::WorkItem*>(ws + lay.items_at);
+  int32_t* flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   const int group = n_q_heads / n_kv_heads;
   if (causal)
     hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, n_items, item_offset, items, reinterpret_cast<int32_t*>(ws + lay.flags_at), (int)lay.capacity);
+                       group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity);
   else
     hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, n_items, item_offset, items, reinterpret_cast<int32_t*>(ws + lay.flags_at), (int)lay.capacity);
+                       group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity);
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
@@ -132,7 +143,7 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   args.v_stride = v_token_stride;
   args.cu_seqlens = cu_seqlens;
   args.items = reinterpret_cast<const hydra::WorkItem*>(ws + lay.items_at);
-  args.n_items = reinterpret_cast<const int32_t*>(ws);
+  args.ctrl = reinterpret_cast<hydra::WorkControl*>(ws);
   args.redo_flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   args.n_q_heads = n_q_heads;
   args.group = n_q_heads / n_kv_heads;
@@ -141,8 +152,9 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;
 
-  (void)causal;
-  const unsigned grid = (unsigned)lay.capacity;
+  // persistent workgroups, one per compute unit (each takes 128 KB of LDS and all 512 registers of its SIMDs)
+  const unsigned grid = compute_units();
+  if (grid == 0) return HYDRA_ERR_LAUNCH;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err;
   switch (head_dim) {

@@ -1,6 +1,5 @@
-// Device prepass: the varlen tile scheduler.  Builds, from cu_seqlens alone, the list of work
-// items the attention kernel consumes, ordered longest first so that the hardware's in-order
-// workgroup dispatch acts as a longest-processing-time scheduler over the 256 CUs.
+// Device prepass: the varlen tile scheduler.  Builds, from cu_seqlens alone, the work list the
+// attention kernel consumes.
 //
 // The paper's Request Processor prepares such per-batch "control parameters" ahead of the GPU
 // work (Section 4.1); here it is a single small kernel on the same stream, so no host
@@ -8,6 +7,14 @@
 //
 // Item = up to 4 consecutive wave tiles of one (sequence, KV head), in the flattened order
 // f = token_tile * group + head_in_group.  Cost = number of 64-key tiles its last wave tile reads.
+//
+// Order of the list.  The chip has 8 dies, each with its own L2 and 32 compute units, and the
+// attention kernel keeps one queue per die.  All items of one (sequence, KV head) pair read the same
+// K/V rows, so a pair goes to ONE queue as a contiguous run (most expensive item first): the
+// workgroups of that die pick the run up together and the rows come from memory once per die
+// instead of once per item.  Pairs are ranked by sequence length, longest first, and dealt to the
+// queues in serpentine order (0..7, 7..0, ...), which keeps the queues' total work level and puts
+// the small items at the end of every queue, where they even out the finish.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -16,21 +23,26 @@
 
 namespace hydra {
 
-constexpr int kCostBuckets = 1024;
 constexpr int kPrepassThreads = 1024;
+constexpr int kPrepassLdsSeqs = 4096;    // sequence lengths kept in LDS for the ranking
+constexpr int kPrepassLdsPrefix = 8192;  // queue prefix entries kept in LDS
 
-// Workspace layout (all int32 unless noted):
-//   [0]            n_items
-//   [4 .. 4+B]     item_offset[b]  exclusive prefix of items per sequence (per KV head), B+1 entries
-//   then, 16-byte aligned, WorkItem[capacity]
-//   then int32 redo_flags[capacity]: all zero between calls; the fast attention kernel sets the
-//   flag of an item it cannot finish exactly, the careful kernel redoes the item and clears it
+// Workspace layout:
+//   WorkControl                          (128 bytes)
+//   int32 sorted_seq[B]                  sequences by descending length
+//   int32 queue_prefix[kXcds][rows]      rows = ceil(B * Hkv / 8): items before the pair of (row, queue) in its queue
+//   WorkItem items[capacity]             16-byte aligned
+//   int32 redo_flags[capacity]           all zero between calls; the fast attention kernel sets the flag
+//                                        of an item it cannot finish exactly, the careful kernel redoes
+//                                        the item and clears it
 struct WorkspaceLayout {
-  size_t offsets_at;  // bytes
-  size_t items_at;    // bytes
-  size_t flags_at;    // bytes
-  size_t capacity;    // items
-  size_t total;       // bytes
+  size_t sorted_at;  // bytes
+  size_t prefix_at;  // bytes
+  size_t items_at;   // bytes
+  size_t flags_at;   // bytes
+  size_t rows;       // pair rows
+  size_t capacity;   // items
+  size_t total;      // bytes
 };
 
 inline size_t item_capacity(int64_t batch, int64_t total_tokens, int64_t n_q_heads, int64_t n_kv_heads) {
@@ -42,8 +54,10 @@ inline size_t item_capacity(int64_t batch, int64_t total_tokens, int64_t n_q_hea
 
 inline WorkspaceLayout workspace_layout(int64_t batch, int64_t total_tokens, int64_t n_q_heads, int64_t n_kv_heads) {
   WorkspaceLayout w;
-  w.offsets_at = 16;
-  size_t end = w.offsets_at + (size_t)(batch + 1) * 4;
+  w.rows = (size_t)((batch * n_kv_heads + kXcds - 1) / kXcds);
+  w.sorted_at = sizeof(WorkControl);
+  w.prefix_at = w.sorted_at + (size_t)batch * 4;
+  const size_t end = w.prefix_at + w.rows * kXcds * 4;
   w.items_at = (end + 15) & ~(size_t)15;
   w.capacity = item_capacity(batch, total_tokens, n_q_heads, n_kv_heads);
   w.flags_at = w.items_at + w.capacity * sizeof(WorkItem);
@@ -56,94 +70,99 @@ __device__ __forceinline__ int items_of_sequence(int len, int group) {
   return (tok_tiles * group + kWavesPerItem - 1) / kWavesPerItem;
 }
 
+// queue of the pair with rank r (row r / 8): serpentine dealing
+__device__ __forceinline__ int pair_rank(int row, int queue) { return row * kXcds + ((row & 1) ? kXcds - 1 - queue : queue); }
+
 template <bool CAUSAL>
 __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch, int n_kv_heads, int group,
-                                                                         int32_t* __restrict__ n_items_out, int32_t* __restrict__ item_offset,
-                                                                         WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags, int capacity) {
-  __shared__ int partial[kPrepassThreads];
-  __shared__ int hist[kCostBuckets];
-  __shared__ int cursor[kCostBuckets];
-  const int tid = threadIdx.x;
+                                                                         WorkControl* __restrict__ ctrl, int32_t* __restrict__ sorted_seq,
+                                                                         int32_t* __restrict__ queue_prefix_global, int rows,
+                                                                         WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags,
+                                                                         int capacity) {
+  __shared__ int s_len[kPrepassLdsSeqs];
+  __shared__ int s_prefix[kPrepassLdsPrefix];
+  __shared__ int s_queue_len[kXcds];
+  __shared__ int s_queue_start[kXcds + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < capacity; i += kPrepassThreads) redo_flags[i] = 0;
+  if (tid < kXcds) ctrl->queue_head[tid] = 0;
+  if (tid == 0) {
+    ctrl->redo_any = 0;
+    ctrl->careful_done = 0;
+  }
 
-  // 1. items per sequence -> exclusive prefix (each thread owns a contiguous run of sequences)
-  const int per_thread = (batch + kPrepassThreads - 1) / kPrepassThreads;
-  const int b_lo = tid * per_thread;
-  const int b_hi = b_lo + per_thread < batch ? b_lo + per_thread : batch;
-  int mine = 0;
-  for (int b = b_lo; b < b_hi; ++b) mine += items_of_sequence(cu[b + 1] - cu[b], group);
-  partial[tid] = mine;
-  for (int i = tid; i < kCostBuckets; i += kPrepassThreads) {
-    hist[i] = 0;
-    cursor[i] = 0;
-  }
+  // 1. rank the sequences by descending length (ties by index): each thread counts who precedes its sequence
+  for (int b = tid; b < batch && b < kPrepassLdsSeqs; b += kPrepassThreads) s_len[b] = cu[b + 1] - cu[b];
   __syncthreads();
-  // Hillis-Steele inclusive scan over the per-thread partial sums
-  for (int d = 1; d < kPrepassThreads; d <<= 1) {
-    const int add = tid >= d ? partial[tid - d] : 0;
-    __syncthreads();
-    partial[tid] += add;
-    __syncthreads();
+  auto length_of = [&](int b) { return b < kPrepassLdsSeqs ? s_len[b] : cu[b + 1] - cu[b]; };
+  for (int b = tid; b < batch; b += kPrepassThreads) {
+    const int mine = length_of(b);
+    int rank = 0;
+    for (int o = 0; o < batch; ++o) {
+      const int other = length_of(o);
+      rank += (other > mine || (other == mine && o < b)) ? 1 : 0;
+    }
+    sorted_seq[rank] = b;
   }
-  int run = partial[tid] - mine;
-  for (int b = b_lo; b < b_hi; ++b) {
-    item_offset[b] = run;
-    run += items_of_sequence(cu[b + 1] - cu[b], group);
-  }
-  const int per_head = partial[kPrepassThreads - 1];
-  if (tid == 0) item_offset[batch] = per_head;
   __threadfence_block();
   __syncthreads();
 
-  int total = per_head * n_kv_heads;
-  if (total > capacity) total = capacity;  // cannot happen for valid cu_seqlens; keeps stores in bounds
-  if (tid == 0) *n_items_out = total;
-  // entries past the end of the list are marked empty (length 0): the attention kernel is launched
-  // over the whole capacity and recognises them without reading the item count
-  for (int i = total + tid; i < capacity; i += kPrepassThreads) items[i] = make_int4(0, 0, 0, 0);
+  // 2. per queue, the running item count over its pairs (one pair per row): wave x scans queue x
+  int* queue_prefix = rows * kXcds <= kPrepassLdsPrefix ? s_prefix : queue_prefix_global;
+  const int n_pairs = batch * n_kv_heads;
+  if (wave < kXcds) {
+    int carry = 0;
+    for (int row0 = 0; row0 < rows; row0 += 64) {
+      const int row = row0 + lane;
+      const int r = pair_rank(row, wave);
+      int n = 0;
+      if (row < rows && r < n_pairs) n = items_of_sequence(length_of(sorted_seq[r / n_kv_heads]), group);
+      int incl = n;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+      }
+      if (row < rows) queue_prefix[wave * rows + row] = carry + incl - n;
+      carry += __shfl(incl, 63);
+    }
+    if (lane == 0) s_queue_len[wave] = carry;
+  }
+  __threadfence_block();
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int x = 0; x < kXcds; ++x) {
+      s_queue_start[x] = run;
+      run += s_queue_len[x];
+    }
+    if (run > capacity) run = capacity;  // cannot happen for valid cu_seqlens; keeps stores in bounds
+    s_queue_start[kXcds] = run;
+    for (int x = 0; x <= kXcds; ++x) ctrl->xcd_start[x] = s_queue_start[x] < run ? s_queue_start[x] : run;
+    ctrl->n_items = run;
+  }
+  __syncthreads();
 
-  // 2. histogram of costs, 3. descending bucket starts, 4. scatter
-  for (int pass = 0; pass < 2; ++pass) {
-    for (int idx = tid; idx < total; idx += kPrepassThreads) {
-      const int kv_head = idx / per_head;
-      const int r = idx - kv_head * per_head;
-      // largest b with item_offset[b] <= r (offsets are non-decreasing; empty sequences repeat)
-      int lo = 0, hi = batch;
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (item_offset[mid] <= r) lo = mid; else hi = mid;
-      }
-      const int b = lo;
-      const int len = cu[b + 1] - cu[b];
-      const int tok_tiles = (len + kWaveTileRows - 1) / kWaveTileRows;
-      const int wave_tiles = tok_tiles * group;
-      const int f0 = (r - item_offset[b]) * kWavesPerItem;
-      const int f_last = f0 + kWavesPerItem - 1 < wave_tiles ? f0 + kWavesPerItem - 1 : wave_tiles - 1;
-      const int cost = CAUSAL ? f_last / group + 1 : tok_tiles;
-      const int bucket = cost < kCostBuckets ? cost : kCostBuckets - 1;
-      if (pass == 0) {
-        atomicAdd(&hist[bucket], 1);
-      } else {
-        const int pos = hist[bucket] + atomicAdd(&cursor[bucket], 1);
-        items[pos] = make_int4(cu[b], len, f0, kv_head);
-      }
+  // 3. one thread per list entry: which queue, which pair (binary search over the queue's rows), which item of the pair
+  const int total = s_queue_start[kXcds];
+  for (int idx = tid; idx < total; idx += kPrepassThreads) {
+    int x = 0;
+    while (x < kXcds - 1 && idx >= s_queue_start[x + 1]) ++x;
+    const int q = idx - s_queue_start[x];
+    const int* pre = queue_prefix + x * rows;
+    int lo = 0, hi = rows;  // largest row with pre[row] <= q (rows with no items repeat the next row's value and sort last)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pre[mid] <= q) lo = mid; else hi = mid;
     }
-    __syncthreads();
-    if (pass == 0) {
-      // counts -> start positions, largest cost first: exclusive scan over reversed buckets
-      static_assert(kCostBuckets == kPrepassThreads, "one bucket per thread");
-      const int n = hist[kCostBuckets - 1 - tid];
-      partial[tid] = n;
-      __syncthreads();
-      for (int d = 1; d < kPrepassThreads; d <<= 1) {
-        const int add = tid >= d ? partial[tid - d] : 0;
-        __syncthreads();
-        partial[tid] += add;
-        __syncthreads();
-      }
-      hist[kCostBuckets - 1 - tid] = partial[tid] - n;
-      __syncthreads();
-    }
+    const int r = pair_rank(lo, x);
+    const int b = sorted_seq[r / n_kv_heads];
+    const int kv_head = r % n_kv_heads;
+    const int start = cu[b], len = cu[b + 1] - start;
+    const int j = q - pre[lo];
+    // most expensive first: under the causal mask the cost grows with the item's position in the sequence
+    const int i = CAUSAL ? items_of_sequence(len, group) - 1 - j : j;
+    items[idx] = make_int4(start, len, i * kWavesPerItem, kv_head);
   }
 }
 
