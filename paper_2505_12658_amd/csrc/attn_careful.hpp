@@ -64,8 +64,14 @@ __device__ __forceinline__ void run_item(const AttnArgs& a, const WorkItem item,
   constexpr int ROWB = G::kRowBytes;
   const int64_t seq_start = item.x;
   const int seq_len = item.y, f0 = item.z, kv_head = item.w;
-  const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
-  const int n_wave_tiles = n_tok_tiles * a.group;
+  // The work item is cut the fast kernel's way: wave tiles of kWaveTileRows query rows, flattened
+  // as token_tile * group + head_in_group.  This kernel works on tiles of 64 rows, so each wave
+  // redoes the 64-row tile that CONTAINS its wave tile; where two waves (or two flagged items)
+  // cover the same rows they store identical values.
+  constexpr int kRows = 64;
+  const int n_fast_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
+  const int n_wave_tiles = n_fast_tiles * a.group;
+  const int n_tok_tiles = (seq_len + kRows - 1) / kRows;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -75,11 +81,12 @@ __device__ __forceinline__ void run_item(const AttnArgs& a, const WorkItem item,
   int f = f0 + wave;
   const bool active = f < n_wave_tiles;
   if (!active) f = n_wave_tiles - 1;
-  const int tok_tile = f / a.group;
-  const int head = kv_head * a.group + (f - tok_tile * a.group);
-  const int q0 = tok_tile * kWaveTileRows;
+  const int fast_tile = f / a.group;
+  const int head = kv_head * a.group + (f - fast_tile * a.group);
+  const int tok_tile = fast_tile * kWaveTileRows / kRows;
+  const int q0 = tok_tile * kRows;
   const int f_last = (f0 + kWavesPerItem - 1 < n_wave_tiles ? f0 + kWavesPerItem - 1 : n_wave_tiles - 1);
-  const int tiles_wg = CAUSAL ? f_last / a.group + 1 : n_tok_tiles;
+  const int tiles_wg = CAUSAL ? (f_last / a.group) * kWaveTileRows / kRows + 1 : n_tok_tiles;
   const int tiles_wave = active ? (CAUSAL ? tok_tile + 1 : n_tok_tiles) : 0;
 
   // first K/V tile in flight before anything else

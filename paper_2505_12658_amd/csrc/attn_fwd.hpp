@@ -48,7 +48,8 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 #define HYDRA_LDS_BYTE(off) ((__attribute__((address_space(3))) unsigned char*)(uintptr_t)(off))
 #define HYDRA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-constexpr int kWaveTileRows = 64;  // query tokens per wave tile
+constexpr int kWaveTileRows = 32;  // query tokens per wave tile
+constexpr int QS = kWaveTileRows / 32;  // 32-query sub-tiles per wave tile
 constexpr int kKvTileRows = 64;    // keys per LDS tile
 constexpr int kWavesPerItem = 4;   // wave tiles per work-list item
 
@@ -98,9 +99,10 @@ struct TileGeom {
   static constexpr int kPvChunks = (D + 31) / 32;                // 32-wide output column blocks of PV
   static constexpr int kTileBytes = kKvTileRows * kRowBytes;     // one K or V tile
   static constexpr int kLoadInstr = kTileBytes / 1024;           // wave-wide 16 B/lane loads per tile
-  // K tiles and V tiles each live in a ring of kRing LDS tiles; loads run kRing - 2 tiles ahead of use
-  static constexpr int kRing = 4;
-  static constexpr int kPrefetch = kRing - 2;
+  // K tiles and V tiles each live in a ring of kRing LDS tiles; loads run kRing - 1 tiles ahead of use
+  // (a tile's slot is free again after the barrier that ends the iteration consuming it)
+  static constexpr int kRing = 2;
+  static constexpr int kPrefetch = kRing - 1;
   static constexpr int kLdsBytes = 2 * kRing * kTileBytes + 64;  // + slack: D=80 reads V columns 80..95
 };
 
@@ -241,17 +243,16 @@ __device__ __forceinline__ void mfma_pv(f32x16_t& O, const bf16x8_t& vf, const b
 }
 // S = A(kf) * B(q) + init, then S += A(kf) * B(q)
 __device__ __forceinline__ void mfma_qk_zero(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "a"(q));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "v"(q));
 }
 __device__ __forceinline__ void mfma_qk_init(f32x16_t& S, const f32x16_t& init, const bf16x8_t& kf, const qreg_t& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(kf), "a"(q), "v"(init));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(kf), "v"(q), "v"(init));
 }
 __device__ __forceinline__ void mfma_qk_acc(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "a"(q));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "v"(q));
 }
-// Move a loaded Q fragment into accumulation registers (tied operand: the compiler emits the copy).
-__device__ __forceinline__ void park_q(qreg_t& home, const qreg_t& loaded) { asm volatile("" : "=a"(home) : "0"(loaded)); }
 // Wait states after the last QK matrix instruction, before anything else touches S.
+__device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[1]) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(S[0])); }
 __device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(S[0]), "+v"(S[1])); }
 
 #endif  // __HIP_DEVICE_COMPILE__
@@ -291,7 +292,7 @@ constexpr int kSlots = 8;             // pipeline slots per key block
 constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_fwd_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using G = TileGeom<D>;
   constexpr int KS = G::kQkSteps;
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // die this workgroup runs on (hardware id register XCC_ID, bits 3:0)
   const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
-  __shared__ int s_claim[8];
+  __shared__ __attribute__((aligned(16))) int s_claim[8];
 
   // Wave 0 claims the items for the whole workgroup, one round ahead: the claim for the next
   // round is issued at the top of a round, resolved (and the item read) before the hot loop, and
@@ -317,6 +318,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   auto post_claim = [&](int idx) {  // wave 0: read the item and post it for the next round
     WorkItem it = make_int4(0, 0, 0, 0);
     if (idx >= 0) it = a.items[idx];
+    // (used by the whole wave right here, so that the load has completed on every code path that
+    // goes on to the hot loop; see the note at pending_claim)
+    it.x = __builtin_amdgcn_readfirstlane(it.x);
+    it.y = __builtin_amdgcn_readfirstlane(it.y);
+    it.z = __builtin_amdgcn_readfirstlane(it.z);
+    it.w = __builtin_amdgcn_readfirstlane(it.w);
     if (lane_id == 0) {
       s_claim[0] = it.x;
       s_claim[1] = it.y;
@@ -342,8 +349,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int kv_head = __builtin_amdgcn_readfirstlane(s_claim[3]);
   const int item_idx = __builtin_amdgcn_readfirstlane(s_claim[4]);
   if (seq_len == 0) break;
-  int pending_claim = 0;  // wave 0, lane 0: position claimed in this die's queue for the next round
-  if (wave == 0 && lane == 0) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc], 1);
+  // Thread 0: position claimed in this die's queue for the next round.  (Written as a per-thread
+  // condition, and read below by every wave, on purpose: the compiler tracks outstanding memory
+  // operations per code path, and an atomic that is "maybe still in flight" on some path into
+  // the hot loop makes it wait for ALL loads there, which would undo the tile prefetch.)
+  int pending_claim = 0;
+  if (threadIdx.x == 0) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc], 1);
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
 
@@ -355,7 +366,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int head = kv_head * a.group + (f - tok_tile * a.group);
   const int q0 = tok_tile * kWaveTileRows;
   const int f_last = (f0 + kWavesPerItem - 1 < n_wave_tiles ? f0 + kWavesPerItem - 1 : n_wave_tiles - 1);
-  const int W = CAUSAL ? f_last / a.group + 1 : n_tok_tiles;  // KV tiles the workgroup streams
+  // KV tiles (of 64 keys) the workgroup streams
+  const int n_kv_tiles = (seq_len + kKvTileRows - 1) / kKvTileRows;
+  const int causal_keys = (f_last / a.group + 1) * kWaveTileRows;  // keys visible to the item's last query tile
+  const int W = CAUSAL && causal_keys < seq_len ? (causal_keys + kKvTileRows - 1) / kKvTileRows : n_kv_tiles;
   // key blocks this wave consumes: keys [0, kv_end)
   const int kv_end = CAUSAL ? (q0 + kWaveTileRows < seq_len ? q0 + kWaveTileRows : seq_len) : seq_len;
   const int NB = active ? (kv_end + kKeyBlock - 1) / kKeyBlock : 0;
@@ -384,11 +398,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
   // parked in accumulation registers.
   const float c = a.scale_log2;
-  qreg_t qf[2][KS];
-  int q_lim[2];  // largest visible key index for this lane's query of sub-tile qs
-  bf16x8_t q_raw[2][KS];
+  qreg_t qf[QS][KS];
+  int q_lim[QS];  // largest visible key index for this lane's query of sub-tile qs
+  bf16x8_t q_raw[QS][KS];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     int row = q0 + 32 * qs + m;
     row = row < seq_len ? row : seq_len - 1;
     q_lim[qs] = CAUSAL ? row : seq_len - 1;
@@ -407,7 +421,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // Q' = bf16(Q * scale * log2 e): the scores come out of the matrix unit in log2 units, and with the
   // accumulator started at -reference the softmax needs one v_exp per score.
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       bf16x8_t scaled;
@@ -418,7 +432,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         scaled[e] = b[0];
         scaled[e + 1] = b[1];
       }
-      park_q(qf[qs][s], __builtin_bit_cast(qreg_t, scaled));
+      qf[qs][s] = __builtin_bit_cast(qreg_t, scaled);
     }
 
   // LDS read addresses: lane part + ring slot of the iteration's K tile / V tile; the key block
@@ -445,9 +459,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int cc = 0; cc < CC; ++cc) v_addr[cc] += dv;
   };
 
-  f32x16_t o_acc[2][CC];
+  f32x16_t o_acc[QS][CC];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
@@ -459,9 +473,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // kMaxLeadLog2 powers of two (far beyond what bf16 activations produce).  A wave that sees a
   // larger lead flags its work item, and the flagged items are recomputed afterwards by the
   // careful kernel, which rescales at every tile.
-  f32x16_t neg_ref[2];                    // -reference, broadcast over the 16 registers of a block
-  float lead[2] = {0.f, 0.f};             // this lane's largest (score - reference) so far
-  float row_sum[2] = {0.f, 0.f};          // this lane's half of the row sum
+  f32x16_t neg_ref[QS];  // -reference, broadcast over the 16 registers of a block
+  float lead[QS];        // this lane's largest (score - reference) so far
+  float row_sum[QS];     // this lane's half of the row sum
+#pragma unroll
+  for (int qs = 0; qs < QS; ++qs) lead[qs] = row_sum[qs] = 0.f;
 
   // LDS fragment reads; rb = key block inside the tile the address registers point at.
   auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
@@ -479,13 +495,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   };
 
   // Mask of key block j (only blocks that reach past a query's limit need it).
-  auto apply_mask = [&](int j, f32x16_t(&S)[2]) {
+  auto apply_mask = [&](int j, f32x16_t(&S)[QS]) {
     const int key0 = j * kKeyBlock;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = key0 + 8 * (r >> 2) + 4 * hf + (r & 3);
 #pragma unroll
-      for (int qs = 0; qs < 2; ++qs)
+      for (int qs = 0; qs < QS; ++qs)
         if (key > q_lim[qs]) S[qs][r] = -__builtin_inff();
     }
   };
@@ -496,7 +512,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // key block whose S already holds (score - reference): exponentials, row sum, rounding to bf16.
   // (The sum is two plain adds on purpose: the 2-element dot-product instruction would halve them,
   // but it runs in the matrix pipe and stalls behind the matrix instructions it is meant to hide in.)
-  auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[2], bf16x8_t(&Pc)[2][2], float(&psum)[2]) __attribute__((always_inline)) {
+  auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[QS], bf16x8_t(&Pc)[QS][2], float(&psum)[QS]) __attribute__((always_inline)) {
     const int qs = pair / 8, r = 2 * (pair % 8);
     f32x2_t pr = {fast_exp2(Sc[qs][r]), fast_exp2(Sc[qs][r + 1])};
     psum[qs] += pr[0];
@@ -514,22 +530,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   //   MFMA : O += V(j-1)^T P(j-1) (P in Pp) and S(j+1) = K(j+1) Q^T (into Sn)
   // One matrix instruction, then the share of vector work that fits in its shadow, and so on:
   // the wave issues in order, so this is what lets the two pipes run side by side.
-  constexpr int NM = 2 * (NQ + NP);  // matrix instructions per step
-  constexpr int NV = 18;             // vector work pieces per step: 2 for the lead check, 16 element pairs
-  auto block_step = [&](auto rb_tag, int j, f32x16_t(&Sc)[2], f32x16_t(&Sn)[2], const bf16x8_t(&Pp)[2][2], bf16x8_t(&Pc)[2][2])
+  constexpr int NM = QS * (NQ + NP);  // matrix instructions per step
+  constexpr int NV = 9 * QS;          // vector work pieces per step: per sub-tile 1 for the lead check, 8 element pairs
+  auto block_step = [&](auto rb_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS], const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2])
                         __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
     if (needs_mask(j)) apply_mask(j, Sc);
-    float psum[2] = {0.f, 0.f};
+    float psum[QS];
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) psum[qs] = 0.f;
     // vector work piece i of this step: 2 pieces track the largest score seen, 16 are softmax pairs
     auto valu_piece = [&](int i) __attribute__((always_inline)) {
-      if (i < 2) {
+      if (i < QS) {
         float t = lead[i];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(t) : "v"(Sc[i][r]), "v"(Sc[i][r + 1]));
         lead[i] = t;
       } else {
-        softmax_pair(i - 2, Sc, Pc, psum);
+        softmax_pair(i - QS, Sc, Pc, psum);
       }
     };
     // fragments one unit ahead
@@ -543,47 +561,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       for (int i = ms_done * NV / NM; i < (ms_done + 1) * NV / NM; ++i) valu_piece(i);
       HYDRA_SCHED_FENCE();
     };
-    constexpr int NU = NQ > NP ? NQ : NP;
-    static_assert(NP >= NQ, "the step must end with PV instructions: they cover the wait states of the last QK result");
+    // Order: QK unit 0, then alternately QK unit u and PV unit u - 1; the step ends with (at least)
+    // two PV units, whose matrix instructions cover the wait states of the last QK result.
+    static_assert(NP >= NQ && NP >= 2, "the step must end with two PV units");
 #pragma unroll
-    for (int u = 0; u < NU; ++u) {
+    for (int u = 0; u <= NP; ++u) {
       if (u < NQ) {
         if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
-        if (u == 0) mfma_qk_init(Sn[0], neg_ref[0], kf_cur, qf[0][u]); else mfma_qk_acc(Sn[0], kf_cur, qf[0][u]);
-        shadow(ms++);
-        if (u == 0) mfma_qk_init(Sn[1], neg_ref[1], kf_cur, qf[1][u]); else mfma_qk_acc(Sn[1], kf_cur, qf[1][u]);
-        shadow(ms++);
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
+          if (u == 0) mfma_qk_init(Sn[qs], neg_ref[qs], kf_cur, qf[qs][u]); else mfma_qk_acc(Sn[qs], kf_cur, qf[qs][u]);
+          shadow(ms++);
+        }
         kf_cur = kf_nxt;
       }
-      if (u < NP) {
-        if (u + 1 < NP) vf_nxt = load_v_frag(RB, u + 1);
-        const int cc = u % CC, s2 = u / CC;
-        mfma_pv(o_acc[0][cc], vf_cur, Pp[0][s2]);
-        shadow(ms++);
-        mfma_pv(o_acc[1][cc], vf_cur, Pp[1][s2]);
-        shadow(ms++);
+      if (u >= 1) {
+        const int pu = u - 1;
+        if (pu + 1 < NP) vf_nxt = load_v_frag(RB, pu + 1);
+        const int cc = pu % CC, s2 = pu / CC;
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
+          mfma_pv(o_acc[qs][cc], vf_cur, Pp[qs][s2]);
+          shadow(ms++);
+        }
         vf_cur = vf_nxt;
       }
     }
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < QS; ++qs) {
       row_sum[qs] += psum[qs];
       asm volatile("" : "+v"(row_sum[qs]));
     }
   };
 
   // PV only (after this wave's last softmax): O += V^T P for key block rb of the V tile in reach
-  auto pv_only = [&](int rb, const bf16x8_t(&Pp)[2][2]) __attribute__((always_inline)) {
+  auto pv_only = [&](int rb, const bf16x8_t(&Pp)[QS][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
       const bf16x8_t vf = load_v_frag(rb, u);
-      mfma_pv(o_acc[0][u % CC], vf, Pp[0][u / CC]);
-      mfma_pv(o_acc[1][u % CC], vf, Pp[1][u / CC]);
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs) mfma_pv(o_acc[qs][u % CC], vf, Pp[qs][u / CC]);
     }
   };
 
-  f32x16_t s_a[2], s_b[2];        // S of even / odd key blocks
-  bf16x8_t p_a[2][2], p_b[2][2];  // P of even / odd key blocks
+  f32x16_t s_a[QS], s_b[QS];        // S of even / odd key blocks
+  bf16x8_t p_a[QS][2], p_b[QS][2];  // P of even / odd key blocks
   using RB0 = std::integral_constant<int, 0>;
   using RB1 = std::integral_constant<int, 1>;
 
@@ -599,13 +621,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {
       const bf16x8_t kf = load_k_frag(0, s);
-      if (s == 0) mfma_qk_zero(s_a[0], kf, qf[0][s]); else mfma_qk_acc(s_a[0], kf, qf[0][s]);
-      if (s == 0) mfma_qk_zero(s_a[1], kf, qf[1][s]); else mfma_qk_acc(s_a[1], kf, qf[1][s]);
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs) {
+        if (s == 0) mfma_qk_zero(s_a[qs], kf, qf[qs][s]); else mfma_qk_acc(s_a[qs], kf, qf[qs][s]);
+      }
     }
     s_results_to_valu(s_a);
     if (needs_mask(0)) apply_mask(0, s_a);
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < QS; ++qs) {
       float t = fmaxf(s_a[qs][0], s_a[qs][1]);
 #pragma unroll
       for (int r = 2; r < 16; ++r) t = fmaxf(t, s_a[qs][r]);
@@ -617,24 +641,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
 #pragma unroll
-    for (int pair = 0; pair < 16; ++pair) softmax_pair(pair, s_a, p_a, row_sum);
+    for (int pair = 0; pair < 8 * QS; ++pair) softmax_pair(pair, s_a, p_a, row_sum);
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {  // (computed even when NB == 1: harmless, never read)
       const bf16x8_t kf = load_k_frag(1, s);
-      if (s == 0) mfma_qk_init(s_b[0], neg_ref[0], kf, qf[0][s]); else mfma_qk_acc(s_b[0], kf, qf[0][s]);
-      if (s == 0) mfma_qk_init(s_b[1], neg_ref[1], kf, qf[1][s]); else mfma_qk_acc(s_b[1], kf, qf[1][s]);
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs) {
+        if (s == 0) mfma_qk_init(s_b[qs], neg_ref[qs], kf, qf[qs][s]); else mfma_qk_acc(s_b[qs], kf, qf[qs][s]);
+      }
     }
     s_results_to_valu(s_b);
   }
   wait_for_iteration(1, 0);
   __syncthreads();
-  int next_idx = -1;
-  WorkItem next_item = make_int4(0, 0, 0, 0);
+  const int pos = __builtin_amdgcn_readfirstlane(pending_claim);  // every wave: the claim has returned (see above)
   if (wave == 0) {
-    const int pos = __builtin_amdgcn_readfirstlane(pending_claim);
     // own queue empty: take from another die's queue (only at the very end of the kernel)
-    next_idx = pos < own_count ? own_begin + pos : claim_item(a.ctrl, xcc, lane);
-    if (next_idx >= 0) next_item = a.items[next_idx];  // (uniform address: a scalar load, held in scalar registers)
+    const int idx = pos < own_count ? own_begin + pos : claim_item(a.ctrl, xcc, lane);
+    // The item itself travels memory -> LDS on its own (one more direct-to-LDS load, lane 0 only):
+    // it is complete when this wave's last wait of the round (for zero loads in flight) has
+    // passed, and the barrier after that wait makes it visible to the other waves.  Every wave
+    // has read this round's claim before the two barriers above, so the slot is free.
+    if (lane == 0) {
+      if (idx >= 0) {
+        const uint64_t base = (uint64_t)(uintptr_t)a.items;
+        u32x4_t rsrc;
+        rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+        rsrc[2] = 0xffffffffu;
+        rsrc[3] = 0x00020000u;
+        const uint32_t off = (uint32_t)idx * (uint32_t)sizeof(WorkItem);
+        const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)HYDRA_LDS_PTR(&s_claim[0]));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(off), "s"(rsrc));
+      } else {
+        s_claim[0] = 0;
+        s_claim[1] = 0;
+        s_claim[2] = 0;
+        s_claim[3] = 0;
+      }
+      s_claim[4] = idx;
+    }
   }
 
   // Per wave: steps 1 .. NB-1.  Iterations 1 .. F run two steps each (the hot loop), iteration
@@ -660,7 +706,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       // stay reserved until those matrix instructions have retired: the compiler takes an assembly
       // statement's outputs as written the moment it issues, and would otherwise hand the registers
       // to other values that the late write-back then overwrites.
-      asm volatile("" : : "v"(s_a[0]), "v"(s_a[1]));
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs) asm volatile("" : : "v"(s_a[qs]));
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
     }
@@ -673,17 +720,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     wait_for_iteration(t + 1, t);
     __syncthreads();
   }
-  // every wave has read this round's claim long ago (there has been at least one barrier since)
-  if (wave == 0 && lane == 0) {
-    s_claim[0] = next_item.x;
-    s_claim[1] = next_item.y;
-    s_claim[2] = next_item.z;
-    s_claim[3] = next_item.w;
-    s_claim[4] = next_idx;
-  }
   // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
   if (NB > 0) {
-    const bool too_far = lead[0] > kMaxLeadLog2 || lead[1] > kMaxLeadLog2;
+    bool too_far = false;
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) too_far = too_far || lead[qs] > kMaxLeadLog2;
     if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) {
       a.redo_flags[item_idx] = 1;
       a.ctrl->redo_any = 1;
@@ -692,7 +733,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // ---- epilogue: normalise, round to bf16, exchange halves so every lane stores 16 bytes ----
   if (active) {
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     const float total = sum_with_other_half(row_sum[qs]);
     const float inv = 1.0f / total;
     const int row = q0 + 32 * qs + m;

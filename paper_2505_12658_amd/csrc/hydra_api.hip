@@ -28,8 +28,11 @@ unsigned compute_units() {
 // The fast kernel over the whole work list, then the careful kernel over whatever it flagged
 // (normally nothing: a few workgroups read the flags and leave).
 template <int D>
-hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned grid, hipStream_t stream) {
-  const unsigned careful_grid = grid;
+hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned compute_units, hipStream_t stream) {
+  // two persistent workgroups per compute unit (each takes half of its registers and LDS): while one
+  // is loading Q, storing O or between key blocks, the other one's matrix work fills the SIMDs
+  const unsigned grid = 2 * compute_units;
+  const unsigned careful_grid = compute_units;
   if (causal) {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
     hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, true>), dim3(careful_grid), dim3(256), 0, stream, args);
@@ -152,7 +155,6 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;
 
-  // persistent workgroups, one per compute unit (each takes 128 KB of LDS and all 512 registers of its SIMDs)
   const unsigned grid = compute_units();
   if (grid == 0) return HYDRA_ERR_LAUNCH;
   hipStream_t s = static_cast<hipStream_t>(stream);

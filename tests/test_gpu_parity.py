@@ -124,6 +124,48 @@ def test_out_of_range_rows_untouched_and_deterministic():
     assert torch.equal(again.view(torch.int16), big[:N].view(torch.int16))
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_large_scores_take_careful_path(d, causal):
+    """Keys planted after the first key block whose scores lead the block-0 maximum by far more than
+    2^60: the fast kernel flags the affected work items and the careful kernel redoes them (if it
+    did not, the flagged rows would be inf/NaN or wrong).  Afterwards the flag words in the
+    workspace are all zero again, and a second call on the same workspace gives the same bits."""
+    hydra = _hydra()
+    w = si.custom([100, 257, 40, 64], 4, 2, d, causal, seed=77)
+    q, k, v = si.make_qkv(w)
+    cu_host = w.cu_seqlens
+    k = k.clone()
+    for b, j in ((0, 50), (1, 200), (3, 33)):       # sequence, key position (>= 32: not in key block 0)
+        k[cu_host[b] + j] = 64.0                    # score = scale * 64 * sum(q): tens of units either way
+    dev = torch.device("cuda:0")
+    cu = torch.from_numpy(cu_host).to(dev)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    ws = hydra.hydra_attn_build_worklist(cu, w.total_tokens, w.max_seqlen, 4, 2, d, causal)
+    out = torch.empty_like(qd)
+    hydra.hydra_attn_varlen_fwd_prebuilt(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, out, ws)
+    torch.cuda.synchronize()
+    want = c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), cu_host, causal, w.softmax_scale)
+    # the planted keys really are out of the fast kernel's range for many rows
+    z = w.softmax_scale * 64.0 * _f64(q).sum(axis=-1)
+    assert (z * 1.4427 > 100).sum() > 50
+    _check(out, want)
+    # workspace: 128-byte control block (int32 [16..25] = queue heads, summary word, counter), sorted
+    # sequences, queue prefixes, then 16-byte items and one int32 flag per item up to the end
+    words = ws.cpu().numpy().view(np.int32)
+    n_items = int(words[0])
+    assert n_items > 0 and (words[16:26] == 0).all()
+    rows = (w.batch * 2 + 7) // 8
+    items_at = (128 + 4 * w.batch + 32 * rows + 15) // 16 * 16
+    capacity = (ws.numel() - items_at) // 20
+    assert capacity >= n_items
+    assert (words[(items_at + 16 * capacity) // 4:] == 0).all()
+    again = torch.empty_like(qd)
+    hydra.hydra_attn_varlen_fwd_prebuilt(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, again, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), out.view(torch.int16))
+
+
 FULL = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode", "qwen2vl_7b_prefill"]
 
 
