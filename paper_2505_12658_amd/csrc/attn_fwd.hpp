@@ -164,18 +164,24 @@ template <int D>
 struct TileLoader {
   using G = TileGeom<D>;
   static constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
-  uint64_t first_row;           // address of row 0 of this sequence / KV head
-  uint32_t total_bytes;         // bytes from first_row to the end of the last valid row
+  // Tiles are issued strictly in order (0, 1, 2, ...), so the descriptor of the next tile is kept
+  // in scalar registers and advanced by one tile after every issue.
+  uint32_t base_lo, base_hi;    // address of the first row of the next tile
+  uint32_t left;                // bytes from there to the end of the sequence's last valid row (0: past the end)
+  uint32_t tile_stride;         // bytes between first rows of consecutive tiles
   uint32_t lane_off[kPerWave];  // bytes from the first row of a tile
-  uint32_t row_bytes;           // token stride in bytes
   int wave;
 
   template <bool IS_V>
   __device__ __forceinline__ void init(const uint16_t* base, int64_t stride, int64_t seq_start, int seq_len, int kv_head, int wave_, int lane) {
     wave = wave_;
-    row_bytes = (uint32_t)(stride * 2);
-    first_row = (uint64_t)(uintptr_t)(base + seq_start * stride + kv_head * D);
-    total_bytes = (uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2);
+    __builtin_assume(wave >= 0 && wave < kWavesPerItem);
+    const uint32_t row_bytes = (uint32_t)(stride * 2);
+    const uint64_t first_row = (uint64_t)(uintptr_t)(base + seq_start * stride + kv_head * D);
+    base_lo = __builtin_amdgcn_readfirstlane((uint32_t)first_row);
+    base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(first_row >> 32));
+    left = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2));
+    tile_stride = __builtin_amdgcn_readfirstlane((uint32_t)kKvTileRows * row_bytes);
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const int flat = (wave + 4 * u) * 64 + lane;
@@ -191,14 +197,12 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) n += (wave + 4 * u < G::kLoadInstr);
     return n;
   }
-  // lds_dst: LDS byte address of the tile's ring slot
-  __device__ __forceinline__ void issue(uint32_t lds_dst, int tile) const {
-    const uint32_t skip = (uint32_t)(tile * kKvTileRows) * row_bytes;
-    const uint64_t base = first_row + skip;
-    const uint32_t left = total_bytes > skip ? total_bytes - skip : 0u;
+  // Issues this wave's loads of the NEXT tile; lds_dst: LDS byte address of the tile's ring slot.
+  __device__ __forceinline__ void issue_next(uint32_t lds_dst) {
     u32x4_t rsrc;
-    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
-    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    // (the values are uniform by construction; the intrinsic states it for the register allocator)
+    rsrc[0] = __builtin_amdgcn_readfirstlane(base_lo);
+    rsrc[1] = __builtin_amdgcn_readfirstlane(base_hi & 0xffffu);
     rsrc[2] = __builtin_amdgcn_readfirstlane(left);
     rsrc[3] = 0x00020000u;
 #pragma unroll
@@ -210,6 +214,10 @@ struct TileLoader {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
       }
     }
+    const uint32_t lo = base_lo + tile_stride;
+    base_hi += lo < base_lo ? 1u : 0u;
+    base_lo = lo;
+    left = left > tile_stride ? left - tile_stride : 0u;
   }
 };
 
@@ -385,15 +393,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int per_tile = k_loader.per_tile();
   // after the issue of iteration t, tile loads 0 .. 2(t+PD) are out; iteration t needs 0 .. 2t
   auto issue_loads = [&](int t) {
-    if (t - 1 + PD < W) v_loader.issue(v_ring + ((t - 1 + PD) % R) * G::kTileBytes, t - 1 + PD);
-    if (t + PD < W) k_loader.issue(k_ring + ((t + PD) % R) * G::kTileBytes, t + PD);
+    if (t - 1 + PD < W) v_loader.issue_next(v_ring + ((t - 1 + PD) % R) * G::kTileBytes);
+    if (t + PD < W) k_loader.issue_next(k_ring + ((t + PD) % R) * G::kTileBytes);
   };
   auto wait_for_iteration = [&](int t_next, int t_issued) {
     const int issued = 2 * (t_issued + PD) + 1 < 2 * W ? 2 * (t_issued + PD) + 1 : 2 * W;
     const int needed = 2 * t_next + 1 < 2 * W ? 2 * t_next + 1 : 2 * W;
     wait_vmcnt_at_most((issued - needed) * per_tile);
   };
-  k_loader.issue(k_ring, 0);
+  k_loader.issue_next(k_ring);
 
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
   // parked in accumulation registers.
@@ -414,8 +422,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
 #pragma unroll
   for (int n = 0; n < PD; ++n) {
-    if (n < W) v_loader.issue(v_ring + n * G::kTileBytes, n);
-    if (n + 1 < W) k_loader.issue(k_ring + (n + 1) * G::kTileBytes, n + 1);
+    if (n < W) v_loader.issue_next(v_ring + n * G::kTileBytes);
+    if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
   }
 
   // Q' = bf16(Q * scale * log2 e): the scores come out of the matrix unit in log2 units, and with the
