@@ -69,8 +69,9 @@ typedef enum {
  *   softmax_scale  finite and >= 0 (normally 1/sqrt(head_dim)).
  *   workspace   device memory, 16-byte aligned, at least hydra_attn_workspace_bytes(...) bytes.  It
  *        receives the tile work list built on the device from cu_seqlens (entries of
- *        (sequence, KV head, first 64-query tile) ordered longest first).  It need not be
- *        initialised and may be reused by the next call on the same stream.
+ *        (sequence, KV head, first query tile), grouped into one queue per accelerator die) and
+ *        a few counters and flags.  It need not be initialised and may be reused by the next
+ *        call on the same stream.
  *
  * batch == 0 or total_tokens == 0 returns HYDRA_OK without launching.
  */
@@ -91,9 +92,9 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
  * into `workspace` (same size rule as above).  hydra_attn_varlen_fwd_prebuilt runs the attention
  * kernel against a workspace filled by an earlier hydra_attn_build_worklist call on the same stream
  * (or one that has completed) with the SAME batch, total_tokens, head counts and causal flag.  It
- * reads the work list and uses a small flag array inside the workspace (left all-zero again when
- * the call's work completes), so two attention calls that share one workspace must not overlap in
- * time.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
+ * reads the work list and uses queue counters and a small flag array inside the workspace (all
+ * left zero again when the call's work completes), so two attention calls that share one workspace
+ * must not overlap in time.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
  */
 int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal,

@@ -1,19 +1,23 @@
 // Fused packed variable-length attention forward for gfx950 (MI355X).
 //
-// One workgroup (4 wavefronts, one per SIMD, up to 512 registers each) runs one work-list item:
-// up to four "wave tiles" that share a sequence and a KV head.  A wave tile is 64 consecutive
-// query tokens of one query head.  K/V tiles of 64 keys stream global -> LDS with direct-to-LDS
-// 128-bit loads into rings of four tiles, and are shared by the four waves.
+// One workgroup (4 wavefronts of 256 registers each) runs one work-list item: up to four "wave
+// tiles" that share a sequence and a KV head.  A wave tile is 32 consecutive query tokens of one
+// query head.  K/V tiles of 64 keys stream global -> LDS with direct-to-LDS 128-bit loads into
+// rings of two tiles (a tile is loaded while the previous one is consumed) and are shared by the
+// four waves.
 //
-// The kernel is persistent: one workgroup per compute unit, each pulling items from the queue of
-// the accelerator die (XCD) it runs on.  The prepass puts all items of one (sequence, KV head)
-// into the same queue, next to each other, so the workgroups that stream the same K/V rows run on
-// the same die at about the same time and share them through that die's L2.
+// The kernel is persistent: two workgroups per compute unit (two waves per SIMD, half of the
+// LDS each), each pulling items from the queue of the accelerator die (XCD) it runs on.  The
+// prepass puts all items of one (sequence, KV head) into the same queue, next to each other, so
+// the workgroups that stream the same K/V rows run on the same die at about the same time and
+// share them through that die's L2.  The two workgroups of a compute unit work on different
+// items: while one loads Q, stores O or waits at a barrier, the other one's matrix instructions
+// fill the SIMDs.
 //
 // Each wave walks its keys in blocks of 32 and software-pipelines three stages, so that the
-// matrix pipe and the vector ALU of its SIMD run side by side (one wave per SIMD: there is no
-// second wave to hide behind): while the VALU does the softmax of block j, the MFMAs issued
-// between its instructions compute S(j+1) = K(j+1) Q^T and O += V(j-1)^T P(j-1).
+// matrix pipe and the vector ALU work side by side also within the wave: while the VALU does the
+// softmax of block j, the MFMAs issued between its instructions compute S(j+1) = K(j+1) Q^T and
+// O += V(j-1)^T P(j-1).
 //
 // Per wave and key block (scores kept transposed so that no cross-lane movement is needed between
 // the two contractions):
@@ -164,12 +168,18 @@ template <int D>
 struct TileLoader {
   using G = TileGeom<D>;
   static constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
+  // When four load instructions cover a whole number of rows, the lane offsets of a wave's loads
+  // differ by a constant (the swizzle repeats), which goes into the instruction's scalar offset:
+  // one offset register instead of kPerWave.
+  static constexpr bool kUniformStep = (4 * 64) % G::kChunks == 0 && ((4 * 64) / G::kChunks) % 16 == 0;
+  static constexpr int kOffsets = kUniformStep ? 1 : kPerWave;
   // Tiles are issued strictly in order (0, 1, 2, ...), so the descriptor of the next tile is kept
   // in scalar registers and advanced by one tile after every issue.
   uint32_t base_lo, base_hi;    // address of the first row of the next tile
   uint32_t left;                // bytes from there to the end of the sequence's last valid row (0: past the end)
   uint32_t tile_stride;         // bytes between first rows of consecutive tiles
-  uint32_t lane_off[kPerWave];  // bytes from the first row of a tile
+  uint32_t lane_off[kOffsets];  // bytes from the first row of a tile
+  uint32_t step_bytes;          // kUniformStep: bytes between the rows of consecutive loads of this wave
   int wave;
 
   template <bool IS_V>
@@ -182,8 +192,9 @@ struct TileLoader {
     base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(first_row >> 32));
     left = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2));
     tile_stride = __builtin_amdgcn_readfirstlane((uint32_t)kKvTileRows * row_bytes);
+    step_bytes = __builtin_amdgcn_readfirstlane((uint32_t)((4 * 64) / G::kChunks) * row_bytes);
 #pragma unroll
-    for (int u = 0; u < kPerWave; ++u) {
+    for (int u = 0; u < kOffsets; ++u) {
       const int flat = (wave + 4 * u) * 64 + lane;
       const int row = flat / G::kChunks, phys = flat % G::kChunks;
       const int chunk = IS_V ? v_swizzle<D>(row, phys) : k_swizzle<D>(row, phys);
@@ -211,7 +222,12 @@ struct TileLoader {
       if (instr < G::kLoadInstr) {
         // (m0 is reserved: the compiler only ever sets it immediately before an instruction of its own that reads it)
         const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + instr * 1024);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
+        if constexpr (kUniformStep) {
+          const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)u * step_bytes);
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(m0), "v"(lane_off[0]), "s"(rsrc), "s"(soff));
+        } else {
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
+        }
       }
     }
     const uint32_t lo = base_lo + tile_stride;
@@ -234,15 +250,18 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n) {
 
 
 // ---- matrix instructions -------------------------------------------------------------------
-// O += V^T P goes through the compiler's builtin: the accumulators live in accumulation
-// registers, which is where the compiler puts every matrix result of a kernel this large, and it
-// inserts the wait states their readers need.
-// S = K Q'^T is written as inline assembly so that its result lands in ordinary registers, where
-// the softmax can read it directly (through the builtin it would arrive in accumulation
-// registers and cost one extra move per score).  The compiler does not see these as matrix
-// instructions, so s_results_to_valu() supplies the wait states between the last of them and
-// the first vector-ALU (or compiler-generated) reader of S; it is issued at the end of every
-// group of QK instructions.  Q is read from accumulation registers.
+// With 256 registers per wave the kernel uses no accumulation registers at all (the compiler
+// splits the budget in two halves as soon as one is needed), so scores and output accumulators
+// live in ordinary registers, where the softmax and the epilogue read them directly.
+// O += V^T P goes through the compiler's builtin, which inserts the wait states the readers of the
+// result need.  S = K Q'^T is written as inline assembly: measured faster at head_dim 128 (the
+// compiler pads every builtin with its own wait states and is freer to move it).  The compiler does
+// not see these as matrix instructions, so
+//   - s_results_to_valu() supplies the wait states between the last of them and the first reader of
+//     S where no other matrix instruction follows (inside the pipeline steps the trailing PV
+//     instructions cover them);
+//   - an output that nobody reads must still be kept reserved until the instruction has retired
+//     (the compiler takes an assembly statement's outputs as written the moment it issues).
 typedef __attribute__((ext_vector_type(4))) uint32_t qreg_t;
 
 // O += A(vf) * B(pf)
@@ -266,9 +285,6 @@ __device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volati
 #endif  // __HIP_DEVICE_COMPILE__
 
 // Scheduling hints: keep the listed instruction classes in this order inside the current region.
-#define HYDRA_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
-#define HYDRA_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
-#define HYDRA_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
 #define HYDRA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // Claims the next unclaimed entry of the work list for the calling workgroup: first from the queue
@@ -296,7 +312,6 @@ __device__ __forceinline__ int claim_item(WorkControl* ctrl, int xcc, int lane) 
 }
 
 constexpr int kKeyBlock = 32;         // keys per pipeline step
-constexpr int kSlots = 8;             // pipeline slots per key block
 constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
 
 template <int D, bool CAUSAL>
@@ -404,7 +419,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   k_loader.issue_next(k_ring);
 
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
-  // parked in accumulation registers.
+  // already scaled (see below).
   const float c = a.scale_log2;
   qreg_t qf[QS][KS];
   int q_lim[QS];  // largest visible key index for this lane's query of sub-tile qs
@@ -540,9 +555,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // the wave issues in order, so this is what lets the two pipes run side by side.
   constexpr int NM = QS * (NQ + NP);  // matrix instructions per step
   constexpr int NV = 9 * QS;          // vector work pieces per step: per sub-tile 1 for the lead check, 8 element pairs
-  auto block_step = [&](auto rb_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS], const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2])
-                        __attribute__((always_inline)) {
+  // qk_tag: false for a wave's last step, which has no S(j+1) to compute.
+  auto block_step = [&](auto rb_tag, auto qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS], const bf16x8_t(&Pp)[QS][2],
+                        bf16x8_t(&Pc)[QS][2]) __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
+    constexpr bool QK = decltype(qk_tag)::value;
+    constexpr int NMS = QK ? NM : QS * NP;       // matrix instructions of this step
     if (needs_mask(j)) apply_mask(j, Sc);
     float psum[QS];
 #pragma unroll
@@ -561,12 +579,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // fragments one unit ahead
     bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt;
     vf_cur = load_v_frag(RB, 0);
-    kf_cur = load_k_frag(RB, 0);
+    if constexpr (QK) kf_cur = load_k_frag(RB, 0);
     int ms = 0;  // matrix-instruction index inside the step
     auto shadow = [&](int ms_done) __attribute__((always_inline)) {
-      // vector pieces [ms*NV/NM, (ms+1)*NV/NM) run behind matrix instruction ms
+      // vector pieces [ms*NV/NMS, (ms+1)*NV/NMS) run behind matrix instruction ms
 #pragma unroll
-      for (int i = ms_done * NV / NM; i < (ms_done + 1) * NV / NM; ++i) valu_piece(i);
+      for (int i = ms_done * NV / NMS; i < (ms_done + 1) * NV / NMS; ++i) valu_piece(i);
       HYDRA_SCHED_FENCE();
     };
     // Order: QK unit 0, then alternately QK unit u and PV unit u - 1; the step ends with (at least)
@@ -574,7 +592,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     static_assert(NP >= NQ && NP >= 2, "the step must end with two PV units");
 #pragma unroll
     for (int u = 0; u <= NP; ++u) {
-      if (u < NQ) {
+      if (QK && u < NQ) {
         if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
@@ -616,6 +634,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   bf16x8_t p_a[QS][2], p_b[QS][2];  // P of even / odd key blocks
   using RB0 = std::integral_constant<int, 0>;
   using RB1 = std::integral_constant<int, 1>;
+  using WithQK = std::integral_constant<bool, true>;
+  using LastStep = std::integral_constant<bool, false>;
 
   {
     const int issued = 2 * PD + 1 < 2 * W ? 2 * PD + 1 : 2 * W;
@@ -699,8 +719,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (; t <= F; ++t) {
     issue_loads(t);
     advance_addresses(t);
-    block_step(RB0{}, 2 * t - 1, s_b, s_a, p_a, p_b);
-    block_step(RB1{}, 2 * t, s_a, s_b, p_b, p_a);
+    block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
+    block_step(RB1{}, WithQK{}, 2 * t, s_a, s_b, p_b, p_a);
     wait_for_iteration(t + 1, t);
     __syncthreads();
   }
@@ -708,14 +728,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     issue_loads(t);
     advance_addresses(t);
     if ((NB - 1) & 1) {
-      block_step(RB0{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
-      pv_only(1, p_b);                               // V block NB - 1 = 2t - 1: second block of V tile t - 1
-      // The step above also produced S(NB) into s_a, which nobody reads.  Its registers must still
-      // stay reserved until those matrix instructions have retired: the compiler takes an assembly
-      // statement's outputs as written the moment it issues, and would otherwise hand the registers
-      // to other values that the late write-back then overwrites.
-#pragma unroll
-      for (int qs = 0; qs < QS; ++qs) asm volatile("" : : "v"(s_a[qs]));
+      block_step(RB0{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
+      pv_only(1, p_b);                                            // V block NB - 1 = 2t - 1: second block of V tile t - 1
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
     }

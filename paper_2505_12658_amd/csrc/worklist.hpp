@@ -80,6 +80,8 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
                                                                          WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags,
                                                                          int capacity) {
   __shared__ int s_len[kPrepassLdsSeqs];
+  __shared__ int s_start[kPrepassLdsSeqs];
+  __shared__ int s_sorted[kPrepassLdsSeqs];
   __shared__ int s_prefix[kPrepassLdsPrefix];
   __shared__ int s_queue_len[kXcds];
   __shared__ int s_queue_start[kXcds + 1];
@@ -91,10 +93,20 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
     ctrl->careful_done = 0;
   }
 
-  // 1. rank the sequences by descending length (ties by index): each thread counts who precedes its sequence
-  for (int b = tid; b < batch && b < kPrepassLdsSeqs; b += kPrepassThreads) s_len[b] = cu[b + 1] - cu[b];
+  // Small batches (the normal case) are handled entirely in LDS after one read of cu_seqlens;
+  // the global arrays are only used for what does not fit.
+  const bool in_lds = batch <= kPrepassLdsSeqs;
+  int* sorted = in_lds ? s_sorted : sorted_seq;
+  for (int b = tid; b < batch && b < kPrepassLdsSeqs; b += kPrepassThreads) {
+    const int start = cu[b];
+    s_start[b] = start;
+    s_len[b] = cu[b + 1] - start;
+  }
   __syncthreads();
   auto length_of = [&](int b) { return b < kPrepassLdsSeqs ? s_len[b] : cu[b + 1] - cu[b]; };
+  auto start_of = [&](int b) { return b < kPrepassLdsSeqs ? s_start[b] : cu[b]; };
+
+  // 1. rank the sequences by descending length (ties by index): each thread counts who precedes its sequence
   for (int b = tid; b < batch; b += kPrepassThreads) {
     const int mine = length_of(b);
     int rank = 0;
@@ -102,7 +114,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
       const int other = length_of(o);
       rank += (other > mine || (other == mine && o < b)) ? 1 : 0;
     }
-    sorted_seq[rank] = b;
+    sorted[rank] = b;
   }
   __threadfence_block();
   __syncthreads();
@@ -116,7 +128,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
       const int row = row0 + lane;
       const int r = pair_rank(row, wave);
       int n = 0;
-      if (row < rows && r < n_pairs) n = items_of_sequence(length_of(sorted_seq[r / n_kv_heads]), group);
+      if (row < rows && r < n_pairs) n = items_of_sequence(length_of(sorted[r / n_kv_heads]), group);
       int incl = n;
 #pragma unroll
       for (int d = 1; d < 64; d <<= 1) {
@@ -130,16 +142,22 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   }
   __threadfence_block();
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
+  {
+    // every thread computes the queue starts for itself; threads 0 .. 8 publish them
+    int run = 0, mine = 0;
+#pragma unroll
     for (int x = 0; x < kXcds; ++x) {
-      s_queue_start[x] = run;
+      if (tid == x) mine = run;
       run += s_queue_len[x];
     }
     if (run > capacity) run = capacity;  // cannot happen for valid cu_seqlens; keeps stores in bounds
-    s_queue_start[kXcds] = run;
-    for (int x = 0; x <= kXcds; ++x) ctrl->xcd_start[x] = s_queue_start[x] < run ? s_queue_start[x] : run;
-    ctrl->n_items = run;
+    if (tid == kXcds) mine = run;
+    if (tid <= kXcds) {
+      if (mine > run) mine = run;
+      s_queue_start[tid] = mine;
+      ctrl->xcd_start[tid] = mine;
+    }
+    if (tid == 0) ctrl->n_items = run;
   }
   __syncthreads();
 
@@ -156,9 +174,9 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
       if (pre[mid] <= q) lo = mid; else hi = mid;
     }
     const int r = pair_rank(lo, x);
-    const int b = sorted_seq[r / n_kv_heads];
+    const int b = sorted[r / n_kv_heads];
     const int kv_head = r % n_kv_heads;
-    const int start = cu[b], len = cu[b + 1] - start;
+    const int start = start_of(b), len = length_of(b);
     const int j = q - pre[lo];
     // most expensive first: under the causal mask the cost grows with the item's position in the sequence
     const int i = CAUSAL ? items_of_sequence(len, group) - 1 - j : j;
