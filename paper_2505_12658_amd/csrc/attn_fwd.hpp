@@ -314,8 +314,12 @@ __device__ __forceinline__ int claim_item(WorkControl* ctrl, int xcc, int lane) 
 constexpr int kKeyBlock = 32;         // keys per pipeline step
 constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
 
+// Persistent workgroups per compute unit (= waves per SIMD): as many as the register file holds.
+template <int D>
+constexpr int kWorkgroupsPerCu = 2;  // (three at head_dim 64 fit the registers, but measured slower)
+
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroupsPerCu<D>, kWorkgroupsPerCu<D>))) void attn_fwd_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using G = TileGeom<D>;
   constexpr int KS = G::kQkSteps;
@@ -576,10 +580,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         softmax_pair(i - QS, Sc, Pc, psum);
       }
     };
-    // fragments one unit ahead
-    bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt;
+    // fragments two units ahead (the LDS answers after roughly two matrix instructions)
+    bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt, kf_nn, vf_nn;
     vf_cur = load_v_frag(RB, 0);
     if constexpr (QK) kf_cur = load_k_frag(RB, 0);
+    if (1 < NP) vf_nxt = load_v_frag(RB, 1);
+    if constexpr (QK) {
+      if (1 < NQ) kf_nxt = load_k_frag(RB, 1);
+    }
     int ms = 0;  // matrix-instruction index inside the step
     auto shadow = [&](int ms_done) __attribute__((always_inline)) {
       // vector pieces [ms*NV/NMS, (ms+1)*NV/NMS) run behind matrix instruction ms
@@ -593,17 +601,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int u = 0; u <= NP; ++u) {
       if (QK && u < NQ) {
-        if (u + 1 < NQ) kf_nxt = load_k_frag(RB, u + 1);
+        if (u + 2 < NQ) kf_nn = load_k_frag(RB, u + 2);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
           if (u == 0) mfma_qk_init(Sn[qs], neg_ref[qs], kf_cur, qf[qs][u]); else mfma_qk_acc(Sn[qs], kf_cur, qf[qs][u]);
           shadow(ms++);
         }
         kf_cur = kf_nxt;
+        kf_nxt = kf_nn;
       }
       if (u >= 1) {
         const int pu = u - 1;
-        if (pu + 1 < NP) vf_nxt = load_v_frag(RB, pu + 1);
+        if (pu + 2 < NP) vf_nn = load_v_frag(RB, pu + 2);
         const int cc = pu % CC, s2 = pu / CC;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
@@ -611,6 +620,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           shadow(ms++);
         }
         vf_cur = vf_nxt;
+        vf_nxt = vf_nn;
       }
     }
 #pragma unroll

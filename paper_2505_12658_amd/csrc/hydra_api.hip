@@ -29,9 +29,9 @@ unsigned compute_units() {
 // (normally nothing: a few workgroups read the flags and leave).
 template <int D>
 hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned compute_units, hipStream_t stream) {
-  // two persistent workgroups per compute unit (each takes half of its registers and LDS): while one
-  // is loading Q, storing O or between key blocks, the other one's matrix work fills the SIMDs
-  const unsigned grid = 2 * compute_units;
+  // two or three persistent workgroups per compute unit (each takes its share of registers and LDS):
+  // while one is loading Q, storing O or between key blocks, the others' matrix work fills the SIMDs
+  const unsigned grid = hydra::kWorkgroupsPerCu<D> * compute_units;
   const unsigned careful_grid = compute_units;
   if (causal) {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
