@@ -27,6 +27,9 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA, 256 CUs x 4096 FLOP/clk x 2
 PEAK_HBM_GBS = 8000.0
 CALIBRATION_COPY_BYTES = 1 << 30
 HEADLINE = "qwen2vl_7b_prefill"
+# HBM bytes per attention-kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes, scaled by the
+# calibration copy (factors 2.000 and 1.000): profiles/attn_fwd_qwen2vl_7b_prefill.md
+MEASURED_TRAFFIC_BYTES = {"qwen2vl_7b_prefill": 287.3e6 + 218.4e6}
 OTHERS = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode"]
 
 
@@ -213,7 +216,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
             "avg_kernel_us": attn_avg * 1e6,
             "min_kernel_us": float(attn_t.min()) * 1e6,
             "hbm_floor_us": w.attention_min_bytes() / (PEAK_HBM_GBS * 1e9) * 1e6,
