@@ -57,8 +57,14 @@ class DeviceBatch:
             self.sets.append(s)
         need = hydra.hydra_attn_workspace_bytes(w.batch, w.total_tokens, w.max_seqlen, w.n_q_heads, w.n_kv_heads, w.head_dim)
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        # The KV scatter does not depend on the attention of the same batch (both only read K/V), so a
+        # serving engine puts it on a second stream: its workgroups fill the compute units that the
+        # attention kernel's persistent workgroups leave as they run out of work.
+        self.side = torch.cuda.Stream(device=dev) if w.kv_cache else None
 
-    def step(self, i: int, events=None):
+    def step(self, i: int, events=None, two_streams=False):
+        """One pass of the whole path over one batch.  two_streams: the KV scatter goes to the side
+        stream, behind the attention launch (call drain() before reading the clock)."""
         h, w, s = self.hydra, self.w, self.sets[i % len(self.sets)]
         h.hydra_attn_build_worklist(self.cu, w.total_tokens, w.max_seqlen, w.n_q_heads, w.n_kv_heads, w.head_dim, w.causal, self.ws)
         if events is not None:
@@ -67,19 +73,22 @@ class DeviceBatch:
         if events is not None:
             events[1].record()
         if w.kv_cache:
-            h.hydra_kv_cache_write(s["k"], s["v"], s["k_cache"], s["v_cache"], s["slots"])
+            if two_streams:
+                h.hydra_kv_cache_write(s["k"], s["v"], s["k_cache"], s["v_cache"], s["slots"], stream=self.side)
+            else:
+                h.hydra_kv_cache_write(s["k"], s["v"], s["k_cache"], s["v_cache"], s["slots"])
             if events is not None:
                 events[2].record()
 
 
-def time_steps(batch: DeviceBatch, steps: int, warmup: int):
-    """Wall-clock over exactly `steps` steps, bracketed by device synchronisation."""
+def time_steps(batch: DeviceBatch, steps: int, warmup: int, two_streams: bool = False):
+    """Wall-clock over exactly `steps` steps, bracketed by device synchronisation (all streams)."""
     for i in range(warmup):
-        batch.step(i)
+        batch.step(i, two_streams=two_streams)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        batch.step(i)
+        batch.step(i, two_streams=two_streams)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
 
@@ -170,6 +179,7 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (cold last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--one-stream", action="store_true", help="time the step with the KV scatter on the attention's stream")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 1 GiB (fp32 x + 0 -> y): the known-size kernel that "
                          "hardware-counter readings of FETCH_SIZE / WRITE_SIZE are scaled by")
@@ -186,7 +196,8 @@ def main():
 
     w = si.WORKLOADS[args.workload]()
     batch = DeviceBatch(w, args.sets, dev)
-    sec_per_step = time_steps(batch, args.steps, args.warmup)
+    sec_one_stream = time_steps(batch, args.steps, args.warmup)
+    sec_per_step = time_steps(batch, args.steps, args.warmup, two_streams=True) if w.kv_cache and not args.one_stream else sec_one_stream
     attn_t, kvw_t = time_kernels(batch, args.steps)
     flops = w.attention_flops()
     attn_avg = float(attn_t.mean())
@@ -206,7 +217,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": describe(w),
-        "step": "work-list build + fused attention" + (" + paged KV write" if w.kv_cache else ""),
+        "step": "work-list build + fused attention" + (" + paged KV write" + ("" if args.one_stream else " (on a second stream)") if w.kv_cache else ""),
+        "ms_per_step_one_stream": sec_one_stream * 1e3,
         "pct_of_bf16_mfma_peak": 100.0 * flops / sec_per_step * 1e-12 / PEAK_BF16_TFLOPS,
         "buffer_sets": args.sets,
         "roofline": {
