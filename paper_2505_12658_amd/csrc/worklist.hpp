@@ -161,26 +161,24 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   }
   __syncthreads();
 
-  // 3. one thread per list entry: which queue, which pair (binary search over the queue's rows), which item of the pair
+  // 3. four threads per pair write the pair's items (thread k takes items k, k + 4, ...): the pair's place in
+  // its queue is known from step 2, so an item costs a few instructions
   const int total = s_queue_start[kXcds];
-  for (int idx = tid; idx < total; idx += kPrepassThreads) {
-    int x = 0;
-    while (x < kXcds - 1 && idx >= s_queue_start[x + 1]) ++x;
-    const int q = idx - s_queue_start[x];
-    const int* pre = queue_prefix + x * rows;
-    int lo = 0, hi = rows;  // largest row with pre[row] <= q (rows with no items repeat the next row's value and sort last)
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (pre[mid] <= q) lo = mid; else hi = mid;
-    }
-    const int r = pair_rank(lo, x);
+  constexpr int kThreadsPerPair = 4;
+  for (int slot = tid / kThreadsPerPair; slot < rows * kXcds; slot += kPrepassThreads / kThreadsPerPair) {
+    const int x = slot / rows, row = slot - x * rows;
+    const int r = pair_rank(row, x);
+    if (r >= n_pairs) continue;
     const int b = sorted[r / n_kv_heads];
     const int kv_head = r % n_kv_heads;
     const int start = start_of(b), len = length_of(b);
-    const int j = q - pre[lo];
-    // most expensive first: under the causal mask the cost grows with the item's position in the sequence
-    const int i = CAUSAL ? items_of_sequence(len, group) - 1 - j : j;
-    items[idx] = make_int4(start, len, i * kWavesPerItem, kv_head);
+    const int n = items_of_sequence(len, group);
+    const int base = s_queue_start[x] + queue_prefix[slot];
+    for (int j = tid % kThreadsPerPair; j < n; j += kThreadsPerPair) {
+      // most expensive first: under the causal mask the cost grows with the item's position in the sequence
+      const int i = CAUSAL ? n - 1 - j : j;
+      if (base + j < total) items[base + j] = make_int4(start, len, i * kWavesPerItem, kv_head);
+    }
   }
 }
 
