@@ -166,6 +166,37 @@ def test_large_scores_take_careful_path(d, causal):
     assert torch.equal(again.view(torch.int16), out.view(torch.int16))
 
 
+def test_many_short_sequences():
+    """More sequences than the work-list builder keeps in LDS (4096): exercises its global-memory path,
+    queue rows beyond one wave, and zero-length sequences in between."""
+    rng = np.random.default_rng(11)
+    lengths = rng.integers(0, 4, size=5000).tolist()
+    lengths[17] = 70
+    lengths[4999] = 33
+    w = si.custom(lengths, 2, 1, 64, True, seed=5)
+    q, k, v = si.make_qkv(w)
+    out = _run_gpu(w, q, k, v)
+    want = c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, True, w.softmax_scale)
+    _check(out, want)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_one_long_sequence(causal):
+    """A single long sequence (many KV tiles per item, ring wrap-around many times), GQA group 3, d = 80."""
+    w = si.custom([4200], 6, 2, 80, causal, seed=9)
+    q, k, v = si.make_qkv(w)
+    out = _run_gpu(w, q, k, v)
+    tokens = np.concatenate([np.arange(0, 40), np.arange(2040, 2120), np.arange(4150, 4200)])
+    rows = [(int(t), h) for t in tokens for h in range(6)]
+    want = c_oracle.attn_rows(_f64(q), _f64(k), _f64(v), w.cu_seqlens, causal, w.softmax_scale, rows)
+    got_all = _f64(out)
+    assert np.isfinite(got_all).all()
+    got = np.stack([got_all[t, h] for t, h in rows])
+    diff = np.abs(got - want)
+    print(f"max abs {diff.max():.3e}  mean abs {diff.mean():.3e}")
+    assert diff.max() <= MAX_ABS and diff.mean() <= MEAN_ABS
+
+
 FULL = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode", "qwen2vl_7b_prefill"]
 
 
