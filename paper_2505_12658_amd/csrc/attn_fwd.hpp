@@ -762,39 +762,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       a.ctrl->redo_any = 1;
     }
   }
-  // ---- epilogue: normalise, round to bf16, exchange halves so every lane stores 16 bytes ----
+  // ---- epilogue: normalise, round to bf16, transpose through LDS, store whole rows ----
+  // In the accumulators a lane owns one query row and scattered groups of 4 columns; stored from
+  // there, one store instruction would touch 32 different rows (one address cycle per row in the
+  // memory pipeline).  So each wave writes its 32 x D tile to a private LDS staging area in K-tile
+  // layout and reads it back with one row per 16 (D = 128) lanes.  Staging area: the K ring, which is
+  // idle between an item's last iteration and the next item's first load (issued after the barrier
+  // at the top of the next round).
+  static_assert(kWavesPerItem * kWaveTileRows * ROWB <= R * G::kTileBytes, "the output tiles of the four waves fit the K ring");
+  static_assert(kWaveTileRows * G::kChunks % 64 == 0, "whole store instructions");
   if (active) {
+    const uint32_t o_stage = k_ring + wave * (kWaveTileRows * ROWB);
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs) {
-    const float total = sum_with_other_half(row_sum[qs]);
-    const float inv = 1.0f / total;
-    const int row = q0 + 32 * qs + m;
-    uint16_t* op = a.out + ((seq_start + (row < seq_len ? row : 0)) * a.n_q_heads + head) * D;
+    for (int qs = 0; qs < QS; ++qs) {
+      const float total = sum_with_other_half(row_sum[qs]);
+      const float inv = 1.0f / total;
+      const int r_own = 32 * qs + m;
 #pragma unroll
-    for (int cc = 0; cc < CC; ++cc)
+      for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
-      for (int pair = 0; pair < 2; ++pair) {
-        // register groups g4 = 2*pair and 2*pair+1 hold columns 32cc + 8*g4 + 4*hf + 0..3
-        uint32_t w[2][2];
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const int r = 4 * (2 * pair + k) + 2 * j;
-            f32x2_t x = {o_acc[qs][cc][r] * inv, o_acc[qs][cc][r + 1] * inv};
-            w[k][j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2_t));
-          }
-        // low half gives its second group and receives the high half's first group:
-        // afterwards a low lane holds columns 8*(2*pair)+0..7, a high lane 8*(2*pair+1)+0..7
-#pragma unroll
-        for (int j = 0; j < 2; ++j) asm volatile("s_nop 3\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 3" : "+v"(w[0][j]), "+v"(w[1][j]));
-        const int col = 32 * cc + 8 * (2 * pair + hf);
-        if (row < seq_len && col < D) {
-          u32x4_t pk = {w[0][0], w[0][1], w[1][0], w[1][1]};
-          *reinterpret_cast<u32x4_t*>(op + col) = pk;
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int chunk = 4 * cc + g4;  // columns 32cc + 8*g4 .. +7; this lane has 4*hf .. 4*hf+3 of them
+          if (chunk >= G::kChunks) continue;
+          f32x2_t x0 = {o_acc[qs][cc][4 * g4] * inv, o_acc[qs][cc][4 * g4 + 1] * inv};
+          f32x2_t x1 = {o_acc[qs][cc][4 * g4 + 2] * inv, o_acc[qs][cc][4 * g4 + 3] * inv};
+          u32x2_t pk = {__builtin_bit_cast(uint32_t, __builtin_convertvector(x0, bf16x2_t)),
+                        __builtin_bit_cast(uint32_t, __builtin_convertvector(x1, bf16x2_t))};
+          *reinterpret_cast<u32x2_t*>(HYDRA_LDS_BYTE(o_stage + r_own * ROWB + k_swizzle<D>(r_own, chunk) * 16 + 8 * hf)) = pk;
         }
-      }
-  }
+    }
+#pragma unroll
+    for (int i = 0; i < kWaveTileRows * G::kChunks / 64; ++i) {
+      const int flat = i * 64 + lane;
+      const int r = flat / G::kChunks, chunk = flat % G::kChunks;
+      const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(HYDRA_LDS_BYTE(o_stage + r * ROWB + k_swizzle<D>(r, chunk) * 16));
+      const int row = q0 + r;
+      if (row < seq_len) *reinterpret_cast<u32x4_t*>(a.out + ((seq_start + row) * a.n_q_heads + head) * D + chunk * 8) = piece;
+    }
   }
   }  // next work item
 #else
