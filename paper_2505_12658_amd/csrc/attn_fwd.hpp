@@ -422,27 +422,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   };
   k_loader.issue_next(k_ring);
 
+  // Q: the wave's 32 rows come in with direct-to-LDS loads that cover whole rows (loaded straight
+  // into the B-operand register layout, one instruction would touch 32 different rows: one address
+  // cycle per row in the memory pipeline), into a private staging area in K-tile layout, and are
+  // read back with the lane pattern of the K reads.  Staging area: the V ring, whose first tile is
+  // loaded after the barrier below.
+  static_assert(kWavesPerItem * kWaveTileRows * ROWB <= R * G::kTileBytes, "the Q tiles of the four waves fit the V ring");
+  const uint32_t q_stage = v_ring + wave * (kWaveTileRows * ROWB);
+  {
+    const uint64_t base = (uint64_t)(uintptr_t)(a.q + (seq_start + q0) * a.q_stride + head * D);
+    const uint32_t q_row_bytes = (uint32_t)(a.q_stride * 2);
+    const int rows = seq_len - q0 < kWaveTileRows ? seq_len - q0 : kWaveTileRows;
+    u32x4_t rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    rsrc[2] = __builtin_amdgcn_readfirstlane((uint32_t)(rows - 1) * q_row_bytes + D * 2);  // rows past the end arrive as zeros
+    rsrc[3] = 0x00020000u;
+#pragma unroll
+    for (int i = 0; i < kWaveTileRows * G::kChunks / 64; ++i) {
+      const int flat = i * 64 + lane;
+      const int row = flat / G::kChunks, phys = flat % G::kChunks;
+      const uint32_t off = (uint32_t)row * q_row_bytes + k_swizzle<D>(row, phys) * 16;
+      const uint32_t m0 = __builtin_amdgcn_readfirstlane(q_stage + i * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(off), "s"(rsrc));
+    }
+  }
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
   // already scaled (see below).
   const float c = a.scale_log2;
   qreg_t qf[QS][KS];
   int q_lim[QS];  // largest visible key index for this lane's query of sub-tile qs
   bf16x8_t q_raw[QS][KS];
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // K(0) and Q have landed (this wave's part)
 #pragma unroll
   for (int qs = 0; qs < QS; ++qs) {
     int row = q0 + 32 * qs + m;
     row = row < seq_len ? row : seq_len - 1;
     q_lim[qs] = CAUSAL ? row : seq_len - 1;
-    const uint16_t* qp = a.q + (seq_start + row) * a.q_stride + head * D + hf * (D / 2);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) q_raw[qs][s] = *reinterpret_cast<const bf16x8_t*>(qp + 8 * s);  // all loads first
-  }
-
-  // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
-#pragma unroll
-  for (int n = 0; n < PD; ++n) {
-    if (n < W) v_loader.issue_next(v_ring + n * G::kTileBytes);
-    if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
+    for (int s = 0; s < KS; ++s)
+      q_raw[qs][s] = *reinterpret_cast<const bf16x8_t*>(HYDRA_LDS_BYTE(q_stage + (32 * qs + m) * ROWB + k_swizzle<D>(32 * qs + m, KS * hf + s) * 16));
   }
 
   // Q' = bf16(Q * scale * log2 e): the scores come out of the matrix unit in log2 units, and with the
@@ -647,10 +666,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   using WithQK = std::integral_constant<bool, true>;
   using LastStep = std::integral_constant<bool, false>;
 
-  {
-    const int issued = 2 * PD + 1 < 2 * W ? 2 * PD + 1 : 2 * W;
-    wait_vmcnt_at_most((issued - 1) * per_tile);  // K(0) and Q have landed
-    __syncthreads();
+  __syncthreads();  // K(0) is complete; every wave has taken its Q out of the V ring
+  // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
+#pragma unroll
+  for (int n = 0; n < PD; ++n) {
+    if (n < W) v_loader.issue_next(v_ring + n * G::kTileBytes);
+    if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
   }
 
   // iteration 0 (not overlapped): S(0) = K(0) Q'^T, reference = row maximum of block 0, softmax of
