@@ -273,7 +273,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_fwd_careful_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[StageGeom<D>::kLdsBytes];
-  if (blockIdx.x == 0 && threadIdx.x < kXcds) a.ctrl->queue_head[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < kXcds) a.ctrl->queue_head[threadIdx.x * kHeadStride] = 0;
   if (__hip_atomic_load(&a.ctrl->redo_any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
   const int n_items = a.ctrl->n_items;
   for (int i = blockIdx.x; i < n_items; i += gridDim.x) {

@@ -69,16 +69,18 @@ constexpr int kXcds = 8;  // accelerator dies; workgroup ids are dealt to them r
 // Control block at the start of the workspace.  The work list is one array; the entries
 // [xcd_start[x], xcd_start[x + 1]) form the queue of die x and queue_head[x] counts how many of
 // them have been claimed in the current attention call.
+// Every queue head has a 128-byte line of its own: the heads are the only words of the workspace
+// that many workgroups update during the kernel, and claims of different dies must not collide.
+constexpr int kHeadStride = 32;  // int32 words between queue heads
 struct WorkControl {
   int32_t n_items;
   int32_t xcd_start[kXcds + 1];
-  int32_t reserved0[6];
-  int32_t queue_head[kXcds];  // zero between calls
-  int32_t redo_any;           // nonzero when some redo flag is set
-  int32_t careful_done;       // workgroups of the careful kernel that have finished (only counted when redo_any)
-  int32_t reserved1[6];
+  int32_t redo_any;      // nonzero when some redo flag is set
+  int32_t careful_done;  // workgroups of the careful kernel that have finished (only counted when redo_any)
+  int32_t reserved[20];
+  int32_t queue_head[kXcds * kHeadStride];  // head of queue x at [x * kHeadStride]; zero between calls
 };
-static_assert(sizeof(WorkControl) == 128, "control block layout");
+static_assert(sizeof(WorkControl) == 128 + kXcds * 128, "control block layout");
 
 struct AttnArgs {
   const uint16_t* q;
@@ -287,28 +289,30 @@ __device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volati
 // Scheduling hints: keep the listed instruction classes in this order inside the current region.
 #define HYDRA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Claims the next unclaimed entry of the work list for the calling workgroup: first from the queue
-// of its own die, and when that one is empty from the next die's queue that still has entries
-// (which keeps the dies level at the end of the kernel).  Called by all lanes of ONE wave; returns
-// the list index, or -1 when every queue is empty.  Heads only grow, so the loop ends.
-__device__ __forceinline__ int claim_item(WorkControl* ctrl, int xcc, int lane) {
-  int y = xcc;
-  for (;;) {
-    const int begin = ctrl->xcd_start[y], end = ctrl->xcd_start[y + 1];
-    int pos = 0;
-    if (lane == 0) pos = atomicAdd(&ctrl->queue_head[y], 1);
-    pos = __builtin_amdgcn_readfirstlane(pos);
-    if (pos < end - begin) return begin + pos;
-    const int z = (xcc + lane) & (kXcds - 1);
-    bool has = false;
-    if (lane < kXcds) {
-      const int head = __hip_atomic_load(&ctrl->queue_head[z], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      has = head < ctrl->xcd_start[z + 1] - ctrl->xcd_start[z];
-    }
-    const uint64_t avail = __builtin_amdgcn_ballot_w64(has);
-    if (avail == 0) return -1;
-    y = (xcc + (int)__builtin_ctzll(avail)) & (kXcds - 1);
+// Claims the next unclaimed entry of queue y.  Called by all lanes of ONE wave; returns the list
+// index, or -1 when the queue is empty.
+__device__ __forceinline__ int claim_from(WorkControl* ctrl, int y, int lane) {
+  const int begin = ctrl->xcd_start[y], end = ctrl->xcd_start[y + 1];
+  int pos = 0;
+  if (lane == 0) pos = atomicAdd(&ctrl->queue_head[y * kHeadStride], 1);
+  pos = __builtin_amdgcn_readfirstlane(pos);
+  return pos < end - begin ? begin + pos : -1;
+}
+
+// A workgroup whose own die's queue is empty helps the other dies: one claim attempt per queue it
+// has not yet found empty (`empty_mask`, kept by the caller), starting at a different neighbour for
+// different workgroups.  Heads only grow, so a queue found empty stays empty and every workgroup
+// makes at most seven failing attempts in its life: no polling, no storm of atomics at the end of
+// the kernel.  Returns the list index or -1 when all queues are empty.
+__device__ __forceinline__ int steal_item(WorkControl* ctrl, int xcc, int first, int lane, uint32_t& empty_mask) {
+  for (int k = 0; k < kXcds - 1; ++k) {
+    const int y = (xcc + 1 + (first + k) % (kXcds - 1)) & (kXcds - 1);
+    if (empty_mask & (1u << y)) continue;
+    const int idx = claim_from(ctrl, y, lane);
+    if (idx >= 0) return idx;
+    empty_mask |= 1u << y;
   }
+  return -1;
 }
 
 constexpr int kKeyBlock = 32;         // keys per pipeline step
@@ -360,7 +364,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
   };
   const int own_begin = a.ctrl->xcd_start[xcc], own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
-  if (wave == 0) post_claim(claim_item(a.ctrl, xcc, lane_id));
+  bool own_empty = false;    // this die's queue has run out (same value in all waves)
+  uint32_t empty_mask = 0;   // wave 0: other dies' queues found empty
+  if (wave == 0) post_claim(claim_from(a.ctrl, xcc, lane_id));
 
   for (;;) {  // one work item per round
   __syncthreads();
@@ -370,6 +376,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   int lane = lane_id;
   asm volatile("" : "+v"(lane));
   const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
+  if (__builtin_amdgcn_readfirstlane(s_claim[1]) == 0) {
+    // Nothing left in this die's queue: take an item from another die's queue.  This is done here, with
+    // the workgroup idle, and synchronously (two memory round trips), not ahead of time like the claims
+    // from the own queue.  Every wave has seen the empty claim before wave 0 overwrites it.
+    own_empty = true;
+    __syncthreads();
+    if (wave == 0) post_claim(steal_item(a.ctrl, xcc, (int)(blockIdx.x >> 3), lane_id, empty_mask));
+    __syncthreads();
+  }
   const int64_t seq_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
   const int seq_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
   const int f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
@@ -380,8 +395,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // condition, and read below by every wave, on purpose: the compiler tracks outstanding memory
   // operations per code path, and an atomic that is "maybe still in flight" on some path into
   // the hot loop makes it wait for ALL loads there, which would undo the tile prefetch.)
-  int pending_claim = 0;
-  if (threadIdx.x == 0) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc], 1);
+  int pending_claim = 0x7fffffff;
+  if (threadIdx.x == 0 && !own_empty) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc * kHeadStride], 1);
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
 
@@ -715,8 +730,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   __syncthreads();
   const int pos = __builtin_amdgcn_readfirstlane(pending_claim);  // every wave: the claim has returned (see above)
   if (wave == 0) {
-    // own queue empty: take from another die's queue (only at the very end of the kernel)
-    const int idx = pos < own_count ? own_begin + pos : claim_item(a.ctrl, xcc, lane);
+    // (own queue empty: an empty claim is posted, and the top of the next round goes stealing)
+    const int idx = pos < own_count ? own_begin + pos : -1;
     // The item itself travels memory -> LDS on its own (one more direct-to-LDS load, lane 0 only):
     // it is complete when this wave's last wait of the round (for zero loads in flight) has
     // passed, and the barrier after that wait makes it visible to the other waves.  Every wave

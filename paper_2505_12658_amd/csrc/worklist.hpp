@@ -28,7 +28,7 @@ constexpr int kPrepassLdsSeqs = 4096;    // sequence lengths kept in LDS for the
 constexpr int kPrepassLdsPrefix = 8192;  // queue prefix entries kept in LDS
 
 // Workspace layout:
-//   WorkControl                          (128 bytes)
+//   WorkControl                          (counts, queue starts, one cache line per queue head)
 //   int32 sorted_seq[B]                  sequences by descending length
 //   int32 queue_prefix[kXcds][rows]      rows = ceil(B * Hkv / 8): items before the pair of (row, queue) in its queue
 //   WorkItem items[capacity]             16-byte aligned
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   __shared__ int s_queue_start[kXcds + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < capacity; i += kPrepassThreads) redo_flags[i] = 0;
-  if (tid < kXcds) ctrl->queue_head[tid] = 0;
+  if (tid < kXcds) ctrl->queue_head[tid * kHeadStride] = 0;
   if (tid == 0) {
     ctrl->redo_any = 0;
     ctrl->careful_done = 0;

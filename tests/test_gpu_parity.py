@@ -150,13 +150,13 @@ def test_large_scores_take_careful_path(d, causal):
     z = w.softmax_scale * 64.0 * _f64(q).sum(axis=-1)
     assert (z * 1.4427 > 100).sum() > 50
     _check(out, want)
-    # workspace: 128-byte control block (int32 [16..25] = queue heads, summary word, counter), sorted
-    # sequences, queue prefixes, then 16-byte items and one int32 flag per item up to the end
+    # workspace: control block (int32 [10], [11] = summary word, counter; queue heads at [32 + 32 x]),
+    # sorted sequences, queue prefixes, then 16-byte items and one int32 flag per item up to the end
     words = ws.cpu().numpy().view(np.int32)
     n_items = int(words[0])
-    assert n_items > 0 and (words[16:26] == 0).all()
+    assert n_items > 0 and words[10] == 0 and words[11] == 0 and (words[32:32 + 256:32] == 0).all()
     rows = (w.batch * 2 + 7) // 8
-    items_at = (128 + 4 * w.batch + 32 * rows + 15) // 16 * 16
+    items_at = (1152 + 4 * w.batch + 32 * rows + 15) // 16 * 16
     capacity = (ws.numel() - items_at) // 20
     assert capacity >= n_items
     assert (words[(items_at + 16 * capacity) // 4:] == 0).all()
