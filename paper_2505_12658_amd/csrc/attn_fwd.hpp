@@ -164,8 +164,11 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 //
 // The load is issued from inline assembly on purpose: when the compiler knows that vector-memory
 // loads write LDS, it makes every later LDS read wait for ALL outstanding loads (vmcnt 0), which
-// would serialise the prefetch ring with the compute.  Completion is tracked by hand instead
-// (wait_vmcnt_at_most + the workgroup barrier before a tile's first reader).
+// would serialise the prefetch ring with the compute.  Completion is tracked by hand instead:
+// every wave waits for ALL of its outstanding loads (wait_all_loads) at the end of the iteration
+// before the one that reads them, followed by the workgroup barrier.  Nothing relies on the order
+// in which direct-to-LDS loads complete: a load that misses to HBM was observed to land after a
+// younger one that hit in L2.
 template <int D>
 struct TileLoader {
   using G = TileGeom<D>;
@@ -239,16 +242,8 @@ struct TileLoader {
   }
 };
 
-// s_waitcnt vmcnt(n) for a run-time n (the count is an immediate): waits until at most n of this
-// wave's vector-memory loads are still in flight.  Rounds down to a supported value (waits longer).
-__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
-#define HYDRA_VMCNT_CASE(k) \
-  if (n >= k) { asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); return; }
-  HYDRA_VMCNT_CASE(24) HYDRA_VMCNT_CASE(18) HYDRA_VMCNT_CASE(16) HYDRA_VMCNT_CASE(12) HYDRA_VMCNT_CASE(9) HYDRA_VMCNT_CASE(8)
-  HYDRA_VMCNT_CASE(6) HYDRA_VMCNT_CASE(4) HYDRA_VMCNT_CASE(3) HYDRA_VMCNT_CASE(2)
-#undef HYDRA_VMCNT_CASE
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
+// Waits until none of this wave's vector-memory operations is in flight.
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 
 // ---- matrix instructions -------------------------------------------------------------------
@@ -320,7 +315,7 @@ constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax referenc
 
 // Persistent workgroups per compute unit (= waves per SIMD): as many as the register file holds.
 template <int D>
-constexpr int kWorkgroupsPerCu = 2;  // (three at head_dim 64 fit the registers, but measured slower)
+constexpr int kWorkgroupsPerCu = D == 64 ? 3 : 2;
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroupsPerCu<D>, kWorkgroupsPerCu<D>))) void attn_fwd_kernel(const AttnArgs a) {
@@ -364,6 +359,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
   };
   const int own_begin = a.ctrl->xcd_start[xcc], own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
+  // Q: a wave's 32 rows come in with direct-to-LDS loads that cover whole rows (loaded straight
+  // into the B-operand register layout, one instruction would touch 32 different rows: one address
+  // cycle per row in the memory pipeline), into a private staging area in K-tile layout, and are
+  // read back with the lane pattern of the K reads.  Staging area: the V ring, which is idle from
+  // an item's last iteration until the barrier before the next item's first key block.  The loads
+  // of the NEXT item are issued as soon as the current item's last iteration is over, ahead of the
+  // epilogue, so that their latency hides behind it.
+  static_assert(kWavesPerItem * kWaveTileRows * ROWB <= R * G::kTileBytes, "the Q tiles of the four waves fit the V ring");
+  constexpr int kRowInstr = kWaveTileRows * G::kChunks / 64;  // 64-lane instructions that cover a 32-row tile
+  static_assert(kWaveTileRows * G::kChunks % 64 == 0, "whole instructions");
+  const uint32_t q_stage = v_ring + wave * (kWaveTileRows * ROWB);
+  auto issue_q_loads = [&](int64_t seq_start, int seq_len, int q0, int head, int lane) {
+    const uint64_t base = (uint64_t)(uintptr_t)(a.q + (seq_start + q0) * a.q_stride + head * D);
+    const uint32_t q_row_bytes = (uint32_t)(a.q_stride * 2);
+    const int rows = seq_len - q0 < kWaveTileRows ? seq_len - q0 : kWaveTileRows;
+    u32x4_t rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    rsrc[2] = __builtin_amdgcn_readfirstlane((uint32_t)(rows - 1) * q_row_bytes + D * 2);  // rows past the end arrive as zeros
+    rsrc[3] = 0x00020000u;
+#pragma unroll
+    for (int i = 0; i < kRowInstr; ++i) {
+      const int flat = i * 64 + lane;
+      const int row = flat / G::kChunks, phys = flat % G::kChunks;
+      const uint32_t off = (uint32_t)row * q_row_bytes + k_swizzle<D>(row, phys) * 16;
+      const uint32_t m0 = __builtin_amdgcn_readfirstlane(q_stage + i * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(off), "s"(rsrc));
+    }
+  };
+  bool q_ahead = false;      // the current item's Q loads were issued at the end of the previous round
   bool own_empty = false;    // this die's queue has run out (same value in all waves)
   uint32_t empty_mask = 0;   // wave 0: other dies' queues found empty
   if (wave == 0) post_claim(claim_from(a.ctrl, xcc, lane_id));
@@ -418,57 +443,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 
   // Workgroup iterations: iteration 0 is the prologue (needs K(0)); iteration t >= 1 needs K tile t
   // and V tile t - 1 and runs, per wave, key-block steps 2t - 1 and 2t.  There are W + 1 of them.
-  // Load order of the whole item: K(0) V(0) K(1) V(1) ... (K(n) is tile load 2n, V(n) is 2n + 1),
-  // issued PD iterations ahead of use.  Loads complete in order, so "tile X has landed" is
-  // "at most (tiles issued after X) * per_tile of this wave's loads are still in flight".
+  // Load order of the whole item: K(0) V(0) K(1) V(1) ..., each tile issued PD = 1 iteration ahead of
+  // its use into the ring slot freed by the barrier that ended the previous iteration; everything
+  // issued in iteration t is needed in iteration t + 1, so each iteration ends with a wait for all
+  // of the wave's loads and a barrier.
   TileLoader<D> k_loader, v_loader;
   k_loader.template init<false>(a.k, a.k_stride, seq_start, seq_len, kv_head, wave, lane);
   v_loader.template init<true>(a.v, a.v_stride, seq_start, seq_len, kv_head, wave, lane);
-  const int per_tile = k_loader.per_tile();
+  static_assert(PD == 1 && R == 2, "the iteration-end wait is for everything in flight");
   // after the issue of iteration t, tile loads 0 .. 2(t+PD) are out; iteration t needs 0 .. 2t
   auto issue_loads = [&](int t) {
     if (t - 1 + PD < W) v_loader.issue_next(v_ring + ((t - 1 + PD) % R) * G::kTileBytes);
     if (t + PD < W) k_loader.issue_next(k_ring + ((t + PD) % R) * G::kTileBytes);
   };
-  auto wait_for_iteration = [&](int t_next, int t_issued) {
-    const int issued = 2 * (t_issued + PD) + 1 < 2 * W ? 2 * (t_issued + PD) + 1 : 2 * W;
-    const int needed = 2 * t_next + 1 < 2 * W ? 2 * t_next + 1 : 2 * W;
-    wait_vmcnt_at_most((issued - needed) * per_tile);
-  };
   k_loader.issue_next(k_ring);
 
-  // Q: the wave's 32 rows come in with direct-to-LDS loads that cover whole rows (loaded straight
-  // into the B-operand register layout, one instruction would touch 32 different rows: one address
-  // cycle per row in the memory pipeline), into a private staging area in K-tile layout, and are
-  // read back with the lane pattern of the K reads.  Staging area: the V ring, whose first tile is
-  // loaded after the barrier below.
-  static_assert(kWavesPerItem * kWaveTileRows * ROWB <= R * G::kTileBytes, "the Q tiles of the four waves fit the V ring");
-  const uint32_t q_stage = v_ring + wave * (kWaveTileRows * ROWB);
-  {
-    const uint64_t base = (uint64_t)(uintptr_t)(a.q + (seq_start + q0) * a.q_stride + head * D);
-    const uint32_t q_row_bytes = (uint32_t)(a.q_stride * 2);
-    const int rows = seq_len - q0 < kWaveTileRows ? seq_len - q0 : kWaveTileRows;
-    u32x4_t rsrc;
-    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
-    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
-    rsrc[2] = __builtin_amdgcn_readfirstlane((uint32_t)(rows - 1) * q_row_bytes + D * 2);  // rows past the end arrive as zeros
-    rsrc[3] = 0x00020000u;
-#pragma unroll
-    for (int i = 0; i < kWaveTileRows * G::kChunks / 64; ++i) {
-      const int flat = i * 64 + lane;
-      const int row = flat / G::kChunks, phys = flat % G::kChunks;
-      const uint32_t off = (uint32_t)row * q_row_bytes + k_swizzle<D>(row, phys) * 16;
-      const uint32_t m0 = __builtin_amdgcn_readfirstlane(q_stage + i * 1024);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(off), "s"(rsrc));
-    }
-  }
+  if (!q_ahead) issue_q_loads(seq_start, seq_len, q0, head, lane);
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
   // already scaled (see below).
   const float c = a.scale_log2;
   qreg_t qf[QS][KS];
   int q_lim[QS];  // largest visible key index for this lane's query of sub-tile qs
   bf16x8_t q_raw[QS][KS];
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // K(0) and Q have landed (this wave's part)
+  wait_all_loads();  // Q (and this wave's part of K(0)) has landed
 #pragma unroll
   for (int qs = 0; qs < QS; ++qs) {
     int row = q0 + 32 * qs + m;
@@ -726,7 +723,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
     s_results_to_valu(s_b);
   }
-  wait_for_iteration(1, 0);
+  wait_all_loads();
   __syncthreads();
   const int pos = __builtin_amdgcn_readfirstlane(pending_claim);  // every wave: the claim has returned (see above)
   if (wave == 0) {
@@ -767,7 +764,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     advance_addresses(t);
     block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
     block_step(RB1{}, WithQK{}, 2 * t, s_a, s_b, p_b, p_a);
-    wait_for_iteration(t + 1, t);
+    wait_all_loads();
     __syncthreads();
   }
   if (NB > 0 && t <= W) {
@@ -779,13 +776,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
     }
-    wait_for_iteration(t + 1, t);
+    wait_all_loads();
     __syncthreads();
     ++t;
   }
   for (; t <= W; ++t) {
     issue_loads(t);
-    wait_for_iteration(t + 1, t);
+    wait_all_loads();
     __syncthreads();
   }
   // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
@@ -798,15 +795,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       a.ctrl->redo_any = 1;
     }
   }
+  // The next item (posted during this round; the last iteration's wait and barrier made it visible):
+  // start its Q loads now.  (When the die's queue has run out the posted claim is empty, and the
+  // item stolen at the top of the next round loads its Q there.)
+  q_ahead = false;
+  {
+    const int next_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
+    if (next_len != 0) {
+      const int64_t next_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
+      const int next_f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
+      const int next_kv = __builtin_amdgcn_readfirstlane(s_claim[3]);
+      const int wave_tiles = ((next_len + kWaveTileRows - 1) / kWaveTileRows) * a.group;
+      const int nf = next_f0 + wave < wave_tiles ? next_f0 + wave : wave_tiles - 1;
+      const int tile = nf / a.group;
+      issue_q_loads(next_start, next_len, tile * kWaveTileRows, next_kv * a.group + (nf - tile * a.group), lane);
+      q_ahead = true;
+    }
+  }
   // ---- epilogue: normalise, round to bf16, transpose through LDS, store whole rows ----
   // In the accumulators a lane owns one query row and scattered groups of 4 columns; stored from
-  // there, one store instruction would touch 32 different rows (one address cycle per row in the
-  // memory pipeline).  So each wave writes its 32 x D tile to a private LDS staging area in K-tile
-  // layout and reads it back with one row per 16 (D = 128) lanes.  Staging area: the K ring, which is
-  // idle between an item's last iteration and the next item's first load (issued after the barrier
-  // at the top of the next round).
+  // there, one store instruction would touch 32 different rows.  So each wave writes its 32 x D
+  // tile to a private LDS staging area in K-tile layout and reads it back with one row per 16
+  // (D = 128) lanes.  Staging area: the K ring, which is idle between an item's last iteration and the
+  // next item's first load (issued after the barrier at the top of the next round).  The stores go
+  // through a buffer descriptor that ends with the tile's last valid row (rows past it are dropped
+  // by the hardware).
   static_assert(kWavesPerItem * kWaveTileRows * ROWB <= R * G::kTileBytes, "the output tiles of the four waves fit the K ring");
-  static_assert(kWaveTileRows * G::kChunks % 64 == 0, "whole store instructions");
   if (active) {
     const uint32_t o_stage = k_ring + wave * (kWaveTileRows * ROWB);
 #pragma unroll
@@ -827,13 +841,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
           *reinterpret_cast<u32x2_t*>(HYDRA_LDS_BYTE(o_stage + r_own * ROWB + k_swizzle<D>(r_own, chunk) * 16 + 8 * hf)) = pk;
         }
     }
+    const uint64_t base = (uint64_t)(uintptr_t)(a.out + ((seq_start + q0) * a.n_q_heads + head) * D);
+    const uint32_t out_row_bytes = (uint32_t)a.n_q_heads * (D * 2);
+    const int rows = seq_len - q0 < kWaveTileRows ? seq_len - q0 : kWaveTileRows;
+    u32x4_t rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    rsrc[2] = __builtin_amdgcn_readfirstlane((uint32_t)(rows - 1) * out_row_bytes + D * 2);
+    rsrc[3] = 0x00020000u;
 #pragma unroll
-    for (int i = 0; i < kWaveTileRows * G::kChunks / 64; ++i) {
+    for (int i = 0; i < kRowInstr; ++i) {
       const int flat = i * 64 + lane;
       const int r = flat / G::kChunks, chunk = flat % G::kChunks;
       const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(HYDRA_LDS_BYTE(o_stage + r * ROWB + k_swizzle<D>(r, chunk) * 16));
-      const int row = q0 + r;
-      if (row < seq_len) *reinterpret_cast<u32x4_t*>(a.out + ((seq_start + row) * a.n_q_heads + head) * D + chunk * 8) = piece;
+      const uint32_t off = (uint32_t)r * out_row_bytes + chunk * 16;
+      // (a store of more than 8 bytes reads its data registers a little after it issues; the wait
+      // states keep the next instruction from overwriting them: the compiler does not see this store)
+      asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 1" : : "v"(piece), "v"(off), "s"(rsrc) : "memory");
     }
   }
   }  // next work item
