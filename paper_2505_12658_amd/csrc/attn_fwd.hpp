@@ -758,8 +758,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // F + 1 runs the odd step left over (if any) and the last P V product, later iterations only
   // keep the workgroup's loads and barriers going.
   const int F = NB > 0 ? (NB - 1) / 2 : 0;
+  // The wave's last step (block NB - 1) has no further scores to compute.  With an odd number of
+  // steps it is the single step of iteration F + 1; with an even number it is the second step of
+  // iteration F, which is therefore run apart from the loop.
+  const bool odd_steps = ((NB - 1) & 1) != 0;
+  const int F_loop = odd_steps ? F : (F > 0 ? F - 1 : 0);
   int t = 1;
-  for (; t <= F; ++t) {
+  for (; t <= F_loop; ++t) {
     issue_loads(t);
     advance_addresses(t);
     block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
@@ -767,10 +772,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     wait_all_loads();
     __syncthreads();
   }
+  if (!odd_steps && F > 0) {
+    issue_loads(t);
+    advance_addresses(t);
+    block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
+    block_step(RB1{}, LastStep{}, 2 * t, s_a, s_b, p_b, p_a);
+    wait_all_loads();
+    __syncthreads();
+    ++t;
+  }
   if (NB > 0 && t <= W) {
     issue_loads(t);
     advance_addresses(t);
-    if ((NB - 1) & 1) {
+    if (odd_steps) {
       block_step(RB0{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
       pv_only(1, p_b);                                            // V block NB - 1 = 2t - 1: second block of V tile t - 1
     } else {
