@@ -1,7 +1,7 @@
 // The careful attention kernel: recomputes the work items the fast kernel flagged.
 //
 // The fast kernel (attn_fwd.hpp) takes every exponential of a row relative to the maximum of the
-// row's first key block; a wave that meets a score leading that reference by more than 2^60 flags
+// row's first key block; a wave whose row sums relative to that reference leave the safe range (2^40) flags
 // its item instead of overflowing.  This kernel redoes such items with the textbook online
 // softmax (running maximum raised, and O rescaled, at every 64-key tile), which is exact for any
 // finite input.  It is not software-pipelined; it exists for correctness, not for speed, and on

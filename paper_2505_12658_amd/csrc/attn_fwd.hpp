@@ -311,7 +311,7 @@ __device__ __forceinline__ int steal_item(WorkControl* ctrl, int xcc, int first,
 }
 
 constexpr int kKeyBlock = 32;         // keys per pipeline step
-constexpr float kMaxLeadLog2 = 60.0f;  // largest lead over the softmax reference the fast kernel accepts
+constexpr float kMaxRowSum = 1.0995116e12f;  // 2^40: largest row sum (relative to the reference) the fast kernel accepts
 
 // Persistent workgroups per compute unit (= waves per SIMD): as many as the register file holds.
 template <int D>
@@ -527,15 +527,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // Softmax reference: the row maximum over key block 0, kept for the whole row.  Every later
   // score accumulator starts at -reference, so the matrix unit hands back (score - reference) in
   // log2 units and the exponential needs no further arithmetic; O never has to be rescaled
-  // inside the loop.  That is exact as long as no later score exceeds the reference by more than
-  // kMaxLeadLog2 powers of two (far beyond what bf16 activations produce).  A wave that sees a
-  // larger lead flags its work item, and the flagged items are recomputed afterwards by the
-  // careful kernel, which rescales at every tile.
+  // inside the loop.  That is exact as long as the exponentials stay far from the end of the fp32
+  // range: a wave whose row sums (which bound every single exponential) exceed kMaxRowSum, or are
+  // not finite, flags its work item, and the flagged items are recomputed afterwards by the careful
+  // kernel, which rescales at every tile.  (bf16 activations lead the first block's maximum by a few
+  // powers of two at most.  Below the limit the unnormalised output is bounded by 2^40 times the sum
+  // of |V| over the keys, so it cannot overflow for |V| up to 10^20.)
   f32x16_t neg_ref[QS];  // -reference, broadcast over the 16 registers of a block
-  float lead[QS];        // this lane's largest (score - reference) so far
   float row_sum[QS];     // this lane's half of the row sum
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs) lead[qs] = row_sum[qs] = 0.f;
+  for (int qs = 0; qs < QS; ++qs) row_sum[qs] = 0.f;
 
   // LDS fragment reads; rb = key block inside the tile the address registers point at.
   auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // One matrix instruction, then the share of vector work that fits in its shadow, and so on:
   // the wave issues in order, so this is what lets the two pipes run side by side.
   constexpr int NM = QS * (NQ + NP);  // matrix instructions per step
-  constexpr int NV = 9 * QS;          // vector work pieces per step: per sub-tile 1 for the lead check, 8 element pairs
+  constexpr int NV = 8 * QS;          // vector work pieces per step: 8 element pairs per sub-tile
   // qk_tag: false for a wave's last step, which has no S(j+1) to compute.
   auto block_step = [&](auto rb_tag, auto qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS], const bf16x8_t(&Pp)[QS][2],
                         bf16x8_t(&Pc)[QS][2]) __attribute__((always_inline)) {
@@ -600,17 +601,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     float psum[QS];
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) psum[qs] = 0.f;
-    // vector work piece i of this step: 2 pieces track the largest score seen, 16 are softmax pairs
-    auto valu_piece = [&](int i) __attribute__((always_inline)) {
-      if (i < QS) {
-        float t = lead[i];
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(t) : "v"(Sc[i][r]), "v"(Sc[i][r + 1]));
-        lead[i] = t;
-      } else {
-        softmax_pair(i - QS, Sc, Pc, psum);
-      }
-    };
+    // vector work piece i of this step: one softmax pair
+    auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_pair(i, Sc, Pc, psum); };
     // fragments two units ahead (the LDS answers after roughly two matrix instructions)
     bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt, kf_nn, vf_nn;
     vf_cur = load_v_frag(RB, 0);
@@ -799,11 +791,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     wait_all_loads();
     __syncthreads();
   }
-  // a score led the reference by too much somewhere in this wave's rows: have the item recomputed
+  // a row sum out of the safe range somewhere in this wave's rows: have the item recomputed
   if (NB > 0) {
     bool too_far = false;
 #pragma unroll
-    for (int qs = 0; qs < QS; ++qs) too_far = too_far || lead[qs] > kMaxLeadLog2;
+    for (int qs = 0; qs < QS; ++qs) too_far = too_far || !(row_sum[qs] <= kMaxRowSum);
     if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) {
       a.redo_flags[item_idx] = 1;
       a.ctrl->redo_any = 1;

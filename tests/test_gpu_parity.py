@@ -128,7 +128,7 @@ def test_out_of_range_rows_untouched_and_deterministic():
 @pytest.mark.parametrize("d", [64, 128])
 def test_large_scores_take_careful_path(d, causal):
     """Keys planted after the first key block whose scores lead the block-0 maximum by far more than
-    2^60: the fast kernel flags the affected work items and the careful kernel redoes them (if it
+    the fast kernel's range (row sums beyond 2^40 times the reference term): it flags the affected work items and the careful kernel redoes them (if it
     did not, the flagged rows would be inf/NaN or wrong).  Afterwards the flag words in the
     workspace are all zero again, and a second call on the same workspace gives the same bits."""
     hydra = _hydra()
