@@ -153,6 +153,37 @@ def cpu_baseline(w: si.Workload, host_qkv, budget_s: float = 15.0):
     }
 
 
+def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode", prefill: str = HEADLINE):
+    """The paper runs the vision encoder and the language model of one instance on two streams
+    (Section 4.3).  Here: encode attention steps on one stream and prefill steps (attention + KV scatter)
+    on another, launched together, against the same steps launched one after the other."""
+    we, wp = si.WORKLOADS[encode](), si.WORKLOADS[prefill]()
+    be, bp = DeviceBatch(we, n_sets, dev), DeviceBatch(wp, n_sets, dev)
+    se, sp = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+
+    def run(concurrent: bool):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            with torch.cuda.stream(se):
+                be.step(i)
+            if not concurrent:
+                sp.wait_stream(se)
+            with torch.cuda.stream(sp):
+                bp.step(i)
+            if not concurrent:
+                se.wait_stream(sp)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    for c in (False, True):
+        run(c)  # warm-up
+    seq, con = run(False), run(True)
+    flops = we.attention_flops() + wp.attention_flops()
+    return {"encode": encode, "prefill": prefill, "steps": steps, "ms_sequential": seq * 1e3, "ms_two_streams": con * 1e3,
+            "tflops_sequential": flops / seq * 1e-12, "tflops_two_streams": flops / con * 1e-12, "speedup": seq / con}
+
+
 def describe(w: si.Workload):
     return {
         "workload": w.name,
@@ -180,6 +211,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--one-stream", action="store_true", help="time the step with the KV scatter on the attention's stream")
+    ap.add_argument("--dual-stream", action="store_true",
+                    help="also measure an encode workload and the prefill workload launched together on two streams "
+                         "against the same two run one after the other (the paper's vision || language streams)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 1 GiB (fp32 x + 0 -> y): the known-size kernel that "
                          "hardware-counter readings of FETCH_SIZE / WRITE_SIZE are scaled by")
@@ -270,6 +304,8 @@ def main():
             torch.cuda.empty_cache()
         result["other_workloads"] = others
 
+    if args.dual_stream:
+        result["dual_stream"] = dual_stream(dev, args.sets, max(20, args.steps // 4))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, host_qkv)
     print(json.dumps(result))
