@@ -213,32 +213,45 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) n += (wave + 4 * u < G::kLoadInstr);
     return n;
   }
-  // Issues this wave's loads of the NEXT tile; lds_dst: LDS byte address of the tile's ring slot.
-  __device__ __forceinline__ void issue_next(uint32_t lds_dst) {
+  // Buffer descriptor of the NEXT tile.  wanted == false: a descriptor of zero bytes (every lane is
+  // out of range: nothing is fetched, and the LDS slot receives zeros).
+  __device__ __forceinline__ u32x4_t next_descriptor(bool wanted = true) const {
     u32x4_t rsrc;
     // (the values are uniform by construction; the intrinsic states it for the register allocator)
     rsrc[0] = __builtin_amdgcn_readfirstlane(base_lo);
     rsrc[1] = __builtin_amdgcn_readfirstlane(base_hi & 0xffffu);
-    rsrc[2] = __builtin_amdgcn_readfirstlane(left);
+    rsrc[2] = __builtin_amdgcn_readfirstlane(wanted ? left : 0u);
     rsrc[3] = 0x00020000u;
-#pragma unroll
-    for (int u = 0; u < kPerWave; ++u) {
-      const int instr = wave + 4 * u;
-      if (instr < G::kLoadInstr) {
-        // (m0 is reserved: the compiler only ever sets it immediately before an instruction of its own that reads it)
-        const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + instr * 1024);
-        if constexpr (kUniformStep) {
-          const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)u * step_bytes);
-          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(m0), "v"(lane_off[0]), "s"(rsrc), "s"(soff));
-        } else {
-          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
-        }
+    return rsrc;
+  }
+  // Issues load u (0 .. kPerWave - 1) of this wave's share of the next tile; lds_dst: LDS byte address
+  // of the tile's ring slot.
+  __device__ __forceinline__ void issue_piece(int u, const u32x4_t& rsrc, uint32_t lds_dst) const {
+    const int instr = wave + 4 * u;
+    if (instr < G::kLoadInstr) {
+      // (m0 is reserved: the compiler only ever sets it immediately before an instruction of its own that reads it)
+      const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + instr * 1024);
+      if constexpr (kUniformStep) {
+        const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)u * step_bytes);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(m0), "v"(lane_off[0]), "s"(rsrc), "s"(soff));
+      } else {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
       }
     }
+  }
+  // Moves on to the tile after the next one.
+  __device__ __forceinline__ void advance() {
     const uint32_t lo = base_lo + tile_stride;
     base_hi += lo < base_lo ? 1u : 0u;
     base_lo = lo;
     left = left > tile_stride ? left - tile_stride : 0u;
+  }
+  // Issues all of this wave's loads of the next tile at once.
+  __device__ __forceinline__ void issue_next(uint32_t lds_dst) {
+    const u32x4_t rsrc = next_descriptor();
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) issue_piece(u, rsrc, lds_dst);
+    advance();
   }
 };
 
@@ -311,6 +324,16 @@ __device__ __forceinline__ int steal_item(WorkControl* ctrl, int xcc, int first,
 }
 
 constexpr int kKeyBlock = 32;         // keys per pipeline step
+
+template <int N>
+using NextRB = std::integral_constant<int, N>;  // key block the following step reads in the same tiles (-1: none)
+
+#if defined(__HIP_DEVICE_COMPILE__)
+// LDS fragments of the first two QK units (k0, k1) and the first two PV units (v0, v1) of a pipeline step.
+struct StepFrags {
+  bf16x8_t k0, k1, v0, v1;
+};
+#endif
 constexpr float kMaxRowSum = 1.0995116e12f;  // 2^40: largest row sum (relative to the reference) the fast kernel accepts
 
 // Persistent workgroups per compute unit (= waves per SIMD): as many as the register file holds.
@@ -592,10 +615,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   constexpr int NM = QS * (NQ + NP);  // matrix instructions per step
   constexpr int NV = 8 * QS;          // vector work pieces per step: 8 element pairs per sub-tile
   // qk_tag: false for a wave's last step, which has no S(j+1) to compute.
-  auto block_step = [&](auto rb_tag, auto qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS], const bf16x8_t(&Pp)[QS][2],
-                        bf16x8_t(&Pc)[QS][2]) __attribute__((always_inline)) {
+  // The LDS fragments of a step's first two QK units and first two PV units are fetched ahead of the
+  // step (the LDS answers after roughly two matrix instructions; fetched at the top of the step that
+  // latency would be exposed once per step): `fr` holds them on entry.  next_tag >= 0: the step that
+  // follows reads key block next_tag of the SAME tiles, and this step's last units fetch its first
+  // fragments into `fr` (next_qk_tag: whether it has QK units).  next_tag < 0: nothing is fetched ahead
+  // (the next tiles are only complete after the iteration's barrier; the caller fetches them then).
+  auto block_step = [&](auto rb_tag, auto qk_tag, auto next_tag, auto next_qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS],
+                        const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2], StepFrags& fr) __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
     constexpr bool QK = decltype(qk_tag)::value;
+    constexpr int NEXT_RB = decltype(next_tag)::value;
+    constexpr bool NEXT_QK = decltype(next_qk_tag)::value;
     constexpr int NMS = QK ? NM : QS * NP;       // matrix instructions of this step
     if (needs_mask(j)) apply_mask(j, Sc);
     float psum[QS];
@@ -603,14 +634,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     for (int qs = 0; qs < QS; ++qs) psum[qs] = 0.f;
     // vector work piece i of this step: one softmax pair
     auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_pair(i, Sc, Pc, psum); };
-    // fragments two units ahead (the LDS answers after roughly two matrix instructions)
-    bf16x8_t kf_cur, vf_cur, kf_nxt, vf_nxt, kf_nn, vf_nn;
-    vf_cur = load_v_frag(RB, 0);
-    if constexpr (QK) kf_cur = load_k_frag(RB, 0);
-    if (1 < NP) vf_nxt = load_v_frag(RB, 1);
-    if constexpr (QK) {
-      if (1 < NQ) kf_nxt = load_k_frag(RB, 1);
-    }
+    bf16x8_t kf_cur = fr.k0, kf_nxt = fr.k1, vf_cur = fr.v0, vf_nxt = fr.v1, kf_nn, vf_nn;
     int ms = 0;  // matrix-instruction index inside the step
     auto shadow = [&](int ms_done) __attribute__((always_inline)) {
       // vector pieces [ms*NV/NMS, (ms+1)*NV/NMS) run behind matrix instruction ms
@@ -625,6 +649,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     for (int u = 0; u <= NP; ++u) {
       if (QK && u < NQ) {
         if (u + 2 < NQ) kf_nn = load_k_frag(RB, u + 2);
+        else if (NEXT_RB >= 0 && NEXT_QK && u + 2 - NQ < NQ) kf_nn = load_k_frag(NEXT_RB, u + 2 - NQ);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
           if (u == 0) mfma_qk_init(Sn[qs], neg_ref[qs], kf_cur, qf[qs][u]); else mfma_qk_acc(Sn[qs], kf_cur, qf[qs][u]);
@@ -636,6 +661,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       if (u >= 1) {
         const int pu = u - 1;
         if (pu + 2 < NP) vf_nn = load_v_frag(RB, pu + 2);
+        else if (NEXT_RB >= 0) vf_nn = load_v_frag(NEXT_RB, pu + 2 - NP);
         const int cc = pu % CC, s2 = pu / CC;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
@@ -651,15 +677,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       row_sum[qs] += psum[qs];
       asm volatile("" : "+v"(row_sum[qs]));
     }
+    if constexpr (NEXT_RB >= 0) {
+      fr.k0 = kf_cur;
+      fr.k1 = kf_nxt;
+      fr.v0 = vf_cur;
+      fr.v1 = vf_nxt;
+    }
+  };
+  // first fragments of a step that reads key block rb of the tiles the address registers point at
+  auto fetch_step_frags = [&](int rb, bool with_qk, StepFrags& fr) __attribute__((always_inline)) {
+    fr.v0 = load_v_frag(rb, 0);
+    if (with_qk) fr.k0 = load_k_frag(rb, 0);
+    fr.v1 = load_v_frag(rb, 1);
+    if (with_qk) fr.k1 = load_k_frag(rb, 1);
   };
 
   // PV only (after this wave's last softmax): O += V^T P for key block rb of the V tile in reach
   auto pv_only = [&](int rb, const bf16x8_t(&Pp)[QS][2]) __attribute__((always_inline)) {
+    // (all fragments are requested before the first matrix instruction: left to itself the compiler
+    // fetches each one right before its use and the wave sits through the LDS latency NP times)
+    bf16x8_t vf[NP];
+#pragma unroll
+    for (int u = 0; u < NP; ++u) vf[u] = load_v_frag(rb, u);
+    HYDRA_SCHED_FENCE();
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
-      const bf16x8_t vf = load_v_frag(rb, u);
 #pragma unroll
-      for (int qs = 0; qs < QS; ++qs) mfma_pv(o_acc[qs][u % CC], vf, Pp[qs][u / CC]);
+      for (int qs = 0; qs < QS; ++qs) mfma_pv(o_acc[qs][u % CC], vf[u], Pp[qs][u / CC]);
     }
   };
 
@@ -681,14 +725,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // iteration 0 (not overlapped): S(0) = K(0) Q'^T, reference = row maximum of block 0, softmax of
   // block 0, S(1) = K(1) Q'^T - reference
   if (NB > 0) {
+    // (the K fragments of both blocks are requested ahead of the matrix instructions that use them,
+    // with scheduling fences in between: see pv_only)
+    bf16x8_t kf0[NQ], kf1[NQ];
+#pragma unroll
+    for (int s = 0; s < NQ; ++s) kf0[s] = load_k_frag(0, s);
+    HYDRA_SCHED_FENCE();
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {
-      const bf16x8_t kf = load_k_frag(0, s);
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs) {
-        if (s == 0) mfma_qk_zero(s_a[qs], kf, qf[qs][s]); else mfma_qk_acc(s_a[qs], kf, qf[qs][s]);
+        if (s == 0) mfma_qk_zero(s_a[qs], kf0[s], qf[qs][s]); else mfma_qk_acc(s_a[qs], kf0[s], qf[qs][s]);
       }
     }
+    HYDRA_SCHED_FENCE();
+#pragma unroll
+    for (int s = 0; s < NQ; ++s) kf1[s] = load_k_frag(1, s);
+    HYDRA_SCHED_FENCE();
     s_results_to_valu(s_a);
     if (needs_mask(0)) apply_mask(0, s_a);
 #pragma unroll
@@ -705,12 +758,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
 #pragma unroll
     for (int pair = 0; pair < 8 * QS; ++pair) softmax_pair(pair, s_a, p_a, row_sum);
+    HYDRA_SCHED_FENCE();
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {  // (computed even when NB == 1: harmless, never read)
-      const bf16x8_t kf = load_k_frag(1, s);
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs) {
-        if (s == 0) mfma_qk_init(s_b[qs], neg_ref[qs], kf, qf[qs][s]); else mfma_qk_acc(s_b[qs], kf, qf[qs][s]);
+        if (s == 0) mfma_qk_init(s_b[qs], neg_ref[qs], kf1[s], qf[qs][s]); else mfma_qk_acc(s_b[qs], kf1[s], qf[qs][s]);
       }
     }
     s_results_to_valu(s_b);
@@ -756,28 +809,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const bool odd_steps = ((NB - 1) & 1) != 0;
   const int F_loop = odd_steps ? F : (F > 0 ? F - 1 : 0);
   int t = 1;
+  StepFrags fr;
   for (; t <= F_loop; ++t) {
-    issue_loads(t);
     advance_addresses(t);
-    block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
-    block_step(RB1{}, WithQK{}, 2 * t, s_a, s_b, p_b, p_a);
+    fetch_step_frags(0, true, fr);
+    HYDRA_SCHED_FENCE();
+    issue_loads(t);
+    block_step(RB0{}, WithQK{}, NextRB<1>{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b, fr);
+    block_step(RB1{}, WithQK{}, NextRB<-1>{}, WithQK{}, 2 * t, s_a, s_b, p_b, p_a, fr);
     wait_all_loads();
     __syncthreads();
   }
   if (!odd_steps && F > 0) {
-    issue_loads(t);
     advance_addresses(t);
-    block_step(RB0{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b);
-    block_step(RB1{}, LastStep{}, 2 * t, s_a, s_b, p_b, p_a);
+    fetch_step_frags(0, true, fr);
+    HYDRA_SCHED_FENCE();
+    issue_loads(t);
+    block_step(RB0{}, WithQK{}, NextRB<1>{}, LastStep{}, 2 * t - 1, s_b, s_a, p_a, p_b, fr);
+    block_step(RB1{}, LastStep{}, NextRB<-1>{}, LastStep{}, 2 * t, s_a, s_b, p_b, p_a, fr);
     wait_all_loads();
     __syncthreads();
     ++t;
   }
   if (NB > 0 && t <= W) {
-    issue_loads(t);
     advance_addresses(t);
     if (odd_steps) {
-      block_step(RB0{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b);  // NB - 1 = 2t - 1
+      fetch_step_frags(0, false, fr);
+      HYDRA_SCHED_FENCE();
+    }
+    issue_loads(t);
+    if (odd_steps) {
+      block_step(RB0{}, LastStep{}, NextRB<-1>{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b, fr);  // NB - 1 = 2t - 1
       pv_only(1, p_b);                                            // V block NB - 1 = 2t - 1: second block of V tile t - 1
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
