@@ -130,6 +130,47 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
                          int32_t total_tokens, int32_t n_kv_heads, int32_t head_dim,
                          int32_t block_size, int64_t num_blocks, void* stream);
 
+/*
+ * Attention of a hybrid batch over the paged KV cache.
+ *
+ * The paper's batch scheduler (Algorithm 1) fills one batch, under a token budget, with the decode
+ * requests (one new token each) and with chunks of prefill requests (get_chunked_size tokens each);
+ * every one of them attends to its request's KV cache, which is paged (Section 5, block size 16 in
+ * Section 5.1).  Request b brings q_len = cu_seqlens_q[b+1] - cu_seqlens_q[b] new tokens and has
+ * kv_lens[b] tokens of context in the cache, the new tokens included (their K/V are written first,
+ * with hydra_kv_cache_write).  For new token i, query head h (KV head hk as above):
+ *     J(i) = {0 .. kv_len - q_len + i}        (causal mask aligned to the END of the context)
+ *     key j lives at cache row  block_tables[b, j / block_size] * block_size + j % block_size
+ *     z_j = softmax_scale * <q[i,h,:], K[j,hk,:]>,  p = softmax over J(i),  out[i,h,:] = sum_j p_j V[j,hk,:]
+ * q_len == kv_len is an ordinary causal prefill, q_len == 1 a decode step.  Arithmetic as in
+ * hydra_attn_varlen_fwd.
+ *
+ *   q    bf16 [total_q, n_q_heads, head_dim], token stride q_token_stride (elements, multiple of 8),
+ *        16-byte aligned.
+ *   out  bf16 [total_q, n_q_heads, head_dim], contiguous, 16-byte aligned.
+ *   k_cache, v_cache  bf16 [num_blocks, block_size, n_kv_heads, head_dim], contiguous, 16-byte aligned.
+ *   block_tables  device int32 [batch, max_blocks_per_seq], row-major; entry [b, n] is the cache block
+ *        that holds keys n*block_size .. of request b.  Only the first ceil(kv_len / block_size)
+ *        entries of a row are read.  Entries must lie in [0, num_blocks) (values outside are clamped
+ *        into the cache, so a bad table gives wrong numbers, not a fault).
+ *   cu_seqlens_q  device int32 [batch + 1], as cu_seqlens above, over the new tokens.
+ *   kv_lens       device int32 [batch]; q_len <= kv_lens[b] <= max_blocks_per_seq * block_size.  A request
+ *        with q_len == 0 (or, invalidly, kv_len < q_len) produces no output.
+ *   max_q_len     upper bound on the q_len of the batch (>= 1); sizes the launch.
+ *   block_size    a power of two, at least 1 (16 in the paper).   head_dim 64, 80 or 128.
+ *   batch and n_kv_heads at most 65535.   No workspace is needed.
+ *
+ * batch == 0 or total_q == 0 returns HYDRA_OK without launching.
+ */
+int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride,
+                         const void* k_cache, const void* v_cache,
+                         const int32_t* block_tables, int32_t max_blocks_per_seq,
+                         const int32_t* cu_seqlens_q, const int32_t* kv_lens,
+                         int32_t batch, int32_t total_q, int32_t max_q_len,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t block_size, int64_t num_blocks,
+                         float softmax_scale, void* stream);
+
 /* Bytes of workspace hydra_attn_varlen_fwd needs for these sizes (0 if the sizes are invalid).
  * Depends only on batch, total_tokens and the head counts; pure host arithmetic. */
 size_t hydra_attn_workspace_bytes(int32_t batch, int32_t total_tokens, int32_t max_seqlen,

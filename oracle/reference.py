@@ -16,7 +16,9 @@ Readings taken where the paper is silent (each also listed in the design notes):
   * packed layout is token-major [N, heads, d] with int32 cu_seqlens of length B + 1;
   * a zero-length sequence is legal and contributes nothing;
   * paged KV cache is [num_blocks, block_size, Hkv, d] per K and per V (block size 16 in the
-    paper's Section 5.1 setup), slot = block * block_size + offset, slot < 0 skips the token.
+    paper's Section 5.1 setup), slot = block * block_size + offset, slot < 0 skips the token;
+  * attention over the paged cache (decode steps and prefill chunks batched by Algorithm 1): the
+    new tokens are the last positions of the request's context and the mask is causal.
 
 Nothing here is tiled, fused or reordered: per (sequence, head) one dense score matrix, one
 explicit boolean mask, one softmax, one matmul.  np.matmul / np.exp are the library steps.
@@ -113,6 +115,68 @@ def attn_rows(q, k, v, cu_seqlens, causal: bool, scale: float, rows) -> np.ndarr
         z = scale * (k[s:e, hk, :] @ q[t, h, :])
         p = masked_softmax(z[None, :], mask_row[None, :])[0]
         out[r] = p @ v[s:e, hk, :]
+    return out
+
+
+def end_aligned_mask(q_len: int, kv_len: int) -> np.ndarray:
+    """Explicit q_len x kv_len boolean matrix for new tokens that sit at the END of a context of
+    kv_len tokens: new token i is context position kv_len - q_len + i and sees every key up to
+    and including itself."""
+    i = np.arange(q_len)[:, None]
+    j = np.arange(kv_len)[None, :]
+    return j <= (kv_len - q_len) + i
+
+
+def attn_paged(q, k_cache, v_cache, block_tables, cu_seqlens_q, kv_lens, scale: float) -> np.ndarray:
+    """Attention of a hybrid batch over the paged KV cache.
+
+    What is computed: the batch that the paper's Algorithm 1 assembles holds decode requests (one
+    new token) and chunks of prefill requests (get_chunked_size new tokens); each attends to its
+    own KV cache, kept in pages (Section 5: paged attention; block size 16 in Section 5.1).  Request
+    b has q_len = cu_seqlens_q[b+1] - cu_seqlens_q[b] new tokens and kv_lens[b] tokens of context
+    in the cache, the new ones included.  Reading taken (the paper does not spell the mask out):
+    the new tokens are the LAST q_len positions of the context and attention is causal, so new
+    token i sees keys 0 .. kv_len - q_len + i.  Key j of request b is cache row
+    (block_tables[b, j // block_size], j % block_size).
+
+    q: [Nq, Hq, d]; caches: [num_blocks, block_size, Hkv, d]; all float64.  Returns [Nq, Hq, d].
+    Per request the context is first gathered from its pages into a dense [kv_len, Hkv, d] array;
+    then one score matrix, one explicit mask, one softmax, one matmul per head.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    kc = np.asarray(k_cache, dtype=np.float64)
+    vc = np.asarray(v_cache, dtype=np.float64)
+    tables = np.asarray(block_tables, dtype=np.int64)
+    cu = np.asarray(cu_seqlens_q, dtype=np.int64)
+    kv_lens = np.asarray(kv_lens, dtype=np.int64)
+    Nq, Hq, d = q.shape
+    num_blocks, bs, Hkv, _ = kc.shape
+    if Hq % Hkv != 0:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    if cu[0] != 0 or cu[-1] != Nq or np.any(np.diff(cu) < 0) or len(kv_lens) != len(cu) - 1:
+        raise ValueError("cu_seqlens_q must start at 0, be non-decreasing and end at the number of new tokens")
+    g = Hq // Hkv
+    out = np.zeros((Nq, Hq, d), dtype=np.float64)
+    for b in range(len(cu) - 1):
+        s, e = int(cu[b]), int(cu[b + 1])
+        Lq, Lk = e - s, int(kv_lens[b])
+        if Lq == 0:
+            continue
+        if Lk < Lq:
+            raise ValueError("a context cannot be shorter than its new tokens")
+        rows = np.arange(Lk)
+        blocks = tables[b, rows // bs]
+        if np.any(blocks < 0) or np.any(blocks >= num_blocks):
+            raise ValueError("block table entry out of range")
+        k_ctx = kc[blocks, rows % bs]  # [Lk, Hkv, d]
+        v_ctx = vc[blocks, rows % bs]
+        mask = end_aligned_mask(Lq, Lk)
+        assert mask.any(axis=1).all(), "every new token sees at least one key"
+        for h in range(Hq):
+            hk = h // g
+            z = scale * (q[s:e, h, :] @ k_ctx[:, hk, :].T)
+            p = masked_softmax(z, mask)
+            out[s:e, h, :] = p @ v_ctx[:, hk, :]
     return out
 
 

@@ -44,6 +44,8 @@ def load_library() -> ctypes.CDLL:
         lib.hydra_attn_build_worklist.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         lib.hydra_kv_cache_write.restype = ctypes.c_int
         lib.hydra_kv_cache_write.argtypes = [vp, vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, i64, vp]
+        lib.hydra_attn_paged_fwd.restype = ctypes.c_int
+        lib.hydra_attn_paged_fwd.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.c_float, vp]
         lib.hydra_attn_workspace_bytes.restype = sz
         lib.hydra_attn_workspace_bytes.argtypes = [i32] * 6
         lib.hydra_status_string.restype = ctypes.c_char_p
@@ -155,3 +157,33 @@ def hydra_kv_cache_write(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor
                                   slot_mapping.data_ptr(), N, Hkv, d, k_cache.shape[1], k_cache.shape[0], _stream_handle(stream))
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_kv_cache_write")
+
+
+def hydra_attn_paged_fwd(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                         cu_seqlens_q: torch.Tensor, kv_lens: torch.Tensor, max_q_len: int, softmax_scale: float,
+                         out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """q [Nq, Hq, d] bf16 (new tokens of all requests, packed); caches [num_blocks, block_size, Hkv, d] bf16 contiguous;
+    block_tables int32 [B, max_blocks_per_seq]; cu_seqlens_q int32 [B+1]; kv_lens int32 [B] (context lengths, new tokens included)."""
+    lib = load_library()
+    _check_token_major(q, "q")
+    if k_cache.dim() != 4 or not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape:
+        raise ValueError("caches must be contiguous [num_blocks, block_size, n_kv_heads, head_dim] of equal shape")
+    if k_cache.dtype != torch.bfloat16 or v_cache.dtype != torch.bfloat16 or not k_cache.is_cuda:
+        raise TypeError("caches must be CUDA bf16 tensors")
+    for t, n in ((block_tables, "block_tables"), (cu_seqlens_q, "cu_seqlens_q"), (kv_lens, "kv_lens")):
+        if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{n} must be a contiguous CUDA int32 tensor")
+    Nq, Hq, d = q.shape
+    batch = cu_seqlens_q.numel() - 1
+    if block_tables.dim() != 2 or block_tables.shape[0] != batch or kv_lens.numel() != batch or k_cache.shape[3] != d:
+        raise ValueError("shape mismatch between q, caches, block_tables, cu_seqlens_q and kv_lens")
+    if out is None:
+        out = torch.empty((Nq, Hq, d), dtype=torch.bfloat16, device=q.device)
+    elif not out.is_contiguous() or out.shape != (Nq, Hq, d) or out.dtype != torch.bfloat16:
+        raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    rc = lib.hydra_attn_paged_fwd(q.data_ptr(), out.data_ptr(), q.stride(0), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
+                                  block_tables.shape[1], cu_seqlens_q.data_ptr(), kv_lens.data_ptr(), batch, Nq, int(max_q_len), Hq,
+                                  k_cache.shape[2], d, k_cache.shape[1], k_cache.shape[0], float(softmax_scale), _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_paged_fwd")
+    return out

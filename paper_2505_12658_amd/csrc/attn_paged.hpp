@@ -1,0 +1,317 @@
+// Attention of a hybrid batch over the paged KV cache (gfx950).
+//
+// The paper's batch scheduler (Algorithm 1) fills one batch, under a token budget, with the decode
+// requests (one new token each) and with chunks of prefill requests (get_chunked_size new tokens
+// each); all of them attend to their request's KV cache, which is paged (Section 5, block size 16).
+// Request b brings q_len new tokens and has kv_len tokens of context in the cache, the new ones
+// included (written beforehand by the paged KV write).  New token i sees keys 0 .. kv_len - q_len + i:
+// the causal mask aligned to the END of the context.  q_len == kv_len is an ordinary prefill,
+// q_len == 1 a decode step.
+//
+// Decomposition: a workgroup of 4 waves takes up to four consecutive wave tiles of one (request, KV
+// head); a wave tile is 64 new tokens of one query head, flattened as f = token_tile * group +
+// head_in_group, so with grouped queries the waves share every K/V tile.  K/V tiles of 64 keys are
+// gathered row by row from the pages (a lane looks its row's page up in the block table, then the
+// 16-byte pieces travel global -> LDS with direct-to-LDS loads) into two stages: tile t + 1 is
+// fetched while tile t is used.  Scores are kept transposed (S^T = K Q^T, O^T += V^T P^T, as in the
+// packed kernel) and the softmax is the textbook online one: running maximum and rescaling at every
+// tile.  One wave per SIMD (the 64 x D output tile plus Q take more than half of the registers).
+// This kernel is a first, plain version: no software pipelining inside the wave, and a decode row
+// occupies a whole 64-row tile.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn_fwd.hpp"
+
+namespace hydra {
+namespace paged {
+
+constexpr int kRows = 64;          // new tokens per wave tile
+constexpr int kWavesPerGroup = 4;  // wave tiles per workgroup
+
+struct PagedArgs {
+  const uint16_t* q;        // [total_q, n_q_heads, D] with token stride
+  uint16_t* out;            // [total_q, n_q_heads, D] contiguous
+  int64_t q_stride;         // elements per token
+  const uint16_t* k_cache;  // [num_blocks, block_size, n_kv_heads, D]
+  const uint16_t* v_cache;
+  const int32_t* block_tables;  // [batch, max_blocks_per_seq]
+  const int32_t* cu_seqlens_q;  // [batch + 1]
+  const int32_t* kv_lens;       // [batch]
+  int32_t max_blocks_per_seq;
+  int32_t num_blocks;
+  int32_t block_shift;  // log2(block_size)
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t group;     // n_q_heads / n_kv_heads
+  float scale_log2;  // softmax_scale * log2(e)
+};
+
+template <int D>
+struct StageGeom {
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kChunks = kRowBytes / 16;
+  static constexpr int kQkSteps = D / 16;
+  static constexpr int kPvChunks = (D + 31) / 32;
+  static constexpr int kTileBytes = kKvTileRows * kRowBytes;  // one K or V tile
+  static constexpr int kStageBytes = 2 * kTileBytes;          // K then V
+  static constexpr int kLoadInstr = kTileBytes / 1024;
+  static constexpr int kLdsBytes = 2 * kStageBytes + 64;      // two stages; slack: D=80 reads V columns 80..95
+};
+
+#if defined(__HIP_DEVICE_COMPILE__)
+// This wave's share of the direct-to-LDS loads of one 64-key K tile and V tile, gathered from the
+// pages.  Keys past the end of the context re-read the last valid key (always masked later).  Block
+// ids are clamped to the cache, so a corrupt table cannot make the loads leave it.
+template <int D>
+__device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const int32_t* table, unsigned char* stage, int wave, int lane,
+                                                    int kv_len, int kv_head, int kv0) {
+  using G = StageGeom<D>;
+  constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
+  const int64_t row_elems = (int64_t)a.n_kv_heads * D;
+  const int in_block = (1 << a.block_shift) - 1;
+#pragma unroll
+  for (int u = 0; u < kPerWave; ++u) {
+    const int instr = wave + 4 * u;
+    if (instr < G::kLoadInstr) {
+      const int flat = instr * 64 + lane;
+      const int row = flat / G::kChunks;
+      const int phys = flat % G::kChunks;
+      int tok = kv0 + row;
+      tok = tok < kv_len ? tok : kv_len - 1;
+      int block = table[tok >> a.block_shift];
+      block = block < 0 ? 0 : (block >= a.num_blocks ? a.num_blocks - 1 : block);
+      const int64_t slot = ((int64_t)block << a.block_shift) + (tok & in_block);
+      const uint16_t* kp = a.k_cache + slot * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
+      const uint16_t* vp = a.v_cache + slot * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + G::kTileBytes + instr * 1024), 16, 0, 0);
+    }
+  }
+}
+#endif  // __HIP_DEVICE_COMPILE__
+
+// grid = (ceil(ceil(max_q_len / 64) * group / 4), n_kv_heads, batch): workgroup (x, y, z) takes wave tiles
+// 4x .. 4x + 3 of request z and KV head y, and leaves at once when the request has fewer.
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_paged_kernel(const PagedArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  using G = StageGeom<D>;
+  constexpr int KS = G::kQkSteps;
+  constexpr int CC = G::kPvChunks;
+  constexpr int ROWB = G::kRowBytes;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
+
+  const int b = blockIdx.z, kv_head = blockIdx.y, f0 = blockIdx.x * kWavesPerGroup;
+  const int64_t q_start = a.cu_seqlens_q[b];
+  const int q_len = a.cu_seqlens_q[b + 1] - (int)q_start;
+  int kv_len = a.kv_lens[b];
+  {
+    // a context longer than the table can describe is cut to the table (never happens for valid input)
+    const int64_t table_keys = (int64_t)a.max_blocks_per_seq << a.block_shift;
+    if (kv_len > table_keys) kv_len = (int)table_keys;
+  }
+  if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
+  const int n_tok_tiles = (q_len + kRows - 1) / kRows;
+  const int n_wave_tiles = n_tok_tiles * a.group;
+  if (f0 >= n_wave_tiles) return;
+  const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
+  const int shift = kv_len - q_len;  // keys that precede the first new token
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
+
+  // this wave's tile
+  int f = f0 + wave;
+  const bool active = f < n_wave_tiles;
+  if (!active) f = n_wave_tiles - 1;
+  const int tok_tile = f / a.group;
+  const int head = kv_head * a.group + (f - tok_tile * a.group);
+  const int q0 = tok_tile * kRows;
+  const int f_last = (f0 + kWavesPerGroup - 1 < n_wave_tiles ? f0 + kWavesPerGroup - 1 : n_wave_tiles - 1);
+  // keys visible to the last new token of a 64-token tile that starts at q: shift + min(q + 64, q_len)
+  auto keys_of_tile = [&](int q) { return shift + (q + kRows < q_len ? q + kRows : q_len); };
+  const int tiles_wg = (keys_of_tile((f_last / a.group) * kRows) + kKvTileRows - 1) / kKvTileRows;
+  const int tiles_wave = active ? (keys_of_tile(q0) + kKvTileRows - 1) / kKvTileRows : 0;
+
+  // first K/V tile in flight before anything else
+  issue_kv_tile_loads<D>(a, table, smem, wave, lane, kv_len, kv_head, 0);
+
+  // Q fragments (B operand): lane (m, hf) holds new token q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7
+  bf16x8_t qf[2][KS];
+  int q_lim[2];  // largest visible key index for this lane's token of sub-tile qs
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    int row = q0 + 32 * qs + m;
+    row = row < q_len ? row : q_len - 1;
+    q_lim[qs] = shift + row;
+    const uint16_t* qp = a.q + (q_start + row) * a.q_stride + head * D + hf * (D / 2);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[qs][s] = *reinterpret_cast<const bf16x8_t*>(qp + 8 * s);
+  }
+
+  // LDS read offsets inside a stage
+  uint32_t k_off[KS], v_off[CC];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) k_off[s] = m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;
+  {
+    const int r = 4 * hf + (sl >> 2);
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc) {
+      const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
+      v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
+    }
+  }
+
+  f32x16_t o_acc[2][CC];
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] = 0.f;
+  float row_max[2] = {-3.0e38f, -3.0e38f};
+  float row_sum[2] = {0.f, 0.f};
+  const float c = a.scale_log2;
+  const int min_lim = shift + q0;  // smallest limit among the tile's tokens
+
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  for (int t = 0; t < tiles_wg; ++t) {
+    unsigned char* stage = smem + (t & 1) * G::kStageBytes;
+    if (t + 1 < tiles_wg)
+      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kStageBytes, wave, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
+
+    if (t < tiles_wave) {
+      const int kv0 = t * kKvTileRows;
+      // ---- S^T = K Q^T ----
+      f32x16_t s_acc[2][2];  // [rb][qs]
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
+        }
+      }
+      // ---- mask (tiles that reach past some token's limit) ----
+      const bool need_mask = kv0 + kKvTileRows - 1 > min_lim;
+      if (need_mask) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+#pragma unroll
+            for (int qs = 0; qs < 2; ++qs)
+              if (key > q_lim[qs]) s_acc[rb][qs][r] = -__builtin_inff();
+          }
+      }
+      // ---- online softmax, P in bf16 ----
+      bf16x8_t p_frag[2][2][2];  // [qs][rb][s2]
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) {
+        float tmax = s_acc[0][qs][0];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[rb][qs][r]);
+        tmax = max_with_other_half(tmax);
+        // (key 0 is visible to every token, so after the first tile the maximum is finite)
+        const float m_new = fmaxf(row_max[qs], tmax);
+        const float alpha = fast_exp2((row_max[qs] - m_new) * c);
+        row_max[qs] = m_new;
+        const float mc = m_new * c;
+        float psum = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          float p[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s_acc[rb][qs][r], c, -mc));
+          if (need_mask) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+              if (key > q_lim[qs]) p[r] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) psum += p[r];
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+              f32x2_t pr = {p[8 * s2 + e], p[8 * s2 + e + 1]};
+              bf16x2_t pb = __builtin_convertvector(pr, bf16x2_t);
+              p_frag[qs][rb][s2][e] = pb[0];
+              p_frag[qs][rb][s2][e + 1] = pb[1];
+            }
+        }
+        row_sum[qs] = row_sum[qs] * alpha + psum;
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] *= alpha;
+      }
+      // ---- O^T += V^T P^T ----
+#pragma unroll
+      for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const unsigned char* vp = stage + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
+            const s16x4_t hi =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
+            typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+            const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, both);
+#pragma unroll
+            for (int qs = 0; qs < 2; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
+          }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+
+  if (!active) return;
+  // ---- epilogue: normalise, round to bf16, store ----
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    const float total = sum_with_other_half(row_sum[qs]);
+    const float inv = 1.0f / total;
+    const int row = q0 + 32 * qs + m;
+    if (row < q_len) {
+      uint16_t* op = a.out + ((q_start + row) * a.n_q_heads + head) * D;
+#pragma unroll
+      for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = 32 * cc + 8 * g4 + 4 * hf;
+          if (col < D) {
+            f32x2_t a0 = {o_acc[qs][cc][4 * g4] * inv, o_acc[qs][cc][4 * g4 + 1] * inv};
+            f32x2_t a1 = {o_acc[qs][cc][4 * g4 + 2] * inv, o_acc[qs][cc][4 * g4 + 3] * inv};
+            const bf16x2_t b0 = __builtin_convertvector(a0, bf16x2_t);
+            const bf16x2_t b1 = __builtin_convertvector(a1, bf16x2_t);
+            u32x2_t pk = {__builtin_bit_cast(uint32_t, b0), __builtin_bit_cast(uint32_t, b1)};
+            *reinterpret_cast<u32x2_t*>(op + col) = pk;
+          }
+        }
+    }
+  }
+#else
+  (void)a;
+#endif
+}
+
+}  // namespace paged
+}  // namespace hydra

@@ -7,6 +7,7 @@
 #include "../../include/hydra_attn.h"
 #include "attn_careful.hpp"
 #include "attn_fwd.hpp"
+#include "attn_paged.hpp"
 #include "kv_write.hpp"
 #include "worklist.hpp"
 
@@ -189,6 +190,55 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
   return hydra_attn_varlen_fwd_prebuilt(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens,
                                         max_seqlen, n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, workspace, workspace_bytes,
                                         stream);
+}
+
+int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const void* k_cache, const void* v_cache,
+                         const int32_t* block_tables, int32_t max_blocks_per_seq, const int32_t* cu_seqlens_q, const int32_t* kv_lens,
+                         int32_t batch, int32_t total_q, int32_t max_q_len, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t block_size, int64_t num_blocks, float softmax_scale, void* stream) {
+  if (batch < 0 || total_q < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0) return HYDRA_ERR_INVALID_ARG;
+  if (!head_dim_supported(head_dim)) return HYDRA_ERR_UNSUPPORTED;
+  if (block_size < 1 || (block_size & (block_size - 1)) != 0) return HYDRA_ERR_UNSUPPORTED;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
+  if (batch == 0 || total_q == 0) return HYDRA_OK;
+  if (max_q_len < 1 || max_blocks_per_seq < 1 || num_blocks < 1) return HYDRA_ERR_INVALID_ARG;
+  if (!q || !out || !k_cache || !v_cache || !block_tables || !cu_seqlens_q || !kv_lens) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_cache) || !aligned16(v_cache)) return HYDRA_ERR_INVALID_ARG;
+  if (q_token_stride < (int64_t)n_q_heads * head_dim || (q_token_stride & 7)) return HYDRA_ERR_INVALID_ARG;
+  if (batch > 65535 || n_kv_heads > 65535 || num_blocks > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  if ((int64_t)max_blocks_per_seq * block_size > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
+
+  hydra::paged::PagedArgs args;
+  args.q = static_cast<const uint16_t*>(q);
+  args.out = static_cast<uint16_t*>(out);
+  args.q_stride = q_token_stride;
+  args.k_cache = static_cast<const uint16_t*>(k_cache);
+  args.v_cache = static_cast<const uint16_t*>(v_cache);
+  args.block_tables = block_tables;
+  args.cu_seqlens_q = cu_seqlens_q;
+  args.kv_lens = kv_lens;
+  args.max_blocks_per_seq = max_blocks_per_seq;
+  args.num_blocks = (int32_t)num_blocks;
+  int shift = 0;
+  while ((1 << shift) < block_size) ++shift;
+  args.block_shift = shift;
+  args.n_q_heads = n_q_heads;
+  args.n_kv_heads = n_kv_heads;
+  args.group = n_q_heads / n_kv_heads;
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;  // (see hydra_attn_varlen_fwd_prebuilt)
+
+  const int64_t tok_tiles = ((int64_t)max_q_len + hydra::paged::kRows - 1) / hydra::paged::kRows;
+  const int64_t groups = (tok_tiles * args.group + hydra::paged::kWavesPerGroup - 1) / hydra::paged::kWavesPerGroup;
+  if (groups > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)groups, (unsigned)n_kv_heads, (unsigned)batch);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (head_dim) {
+    case 64: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), 0, s, args); break;
+    case 80: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<80>, grid, dim3(256), 0, s, args); break;
+    default: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<128>, grid, dim3(256), 0, s, args); break;
+  }
+  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, int64_t v_token_stride, void* k_cache, void* v_cache,

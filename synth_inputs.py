@@ -132,6 +132,97 @@ WORKLOADS = {
 }
 
 
+@dataclass
+class HybridBatch:
+    """One batch of the paper's Algorithm 1: decode requests (one new token) and chunks of prefill
+    requests, each attending to its own paged KV cache.  q_lens[b] new tokens, kv_lens[b] tokens of
+    context with the new ones included."""
+    name: str
+    q_lens: List[int]
+    kv_lens: List[int]
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    block_size: int = 16
+    seed: int = 0
+    cu_seqlens_q: np.ndarray = field(init=False)
+
+    def __post_init__(self):
+        assert len(self.q_lens) == len(self.kv_lens) and all(k >= q >= 0 for q, k in zip(self.q_lens, self.kv_lens))
+        self.cu_seqlens_q = np.concatenate([[0], np.cumsum(self.q_lens)]).astype(np.int32)
+
+    @property
+    def batch(self) -> int:
+        return len(self.q_lens)
+
+    @property
+    def total_q(self) -> int:
+        return int(self.cu_seqlens_q[-1])
+
+    @property
+    def max_q_len(self) -> int:
+        return max(self.q_lens) if self.q_lens else 0
+
+    @property
+    def softmax_scale(self) -> float:
+        return 1.0 / math.sqrt(self.head_dim)
+
+    def visible_pairs(self) -> int:
+        """New token i of a request sees kv - q + i + 1 keys: q (kv - q) + q (q + 1) / 2 per request."""
+        return sum(q * (k - q) + q * (q + 1) // 2 for q, k in zip(self.q_lens, self.kv_lens))
+
+    def attention_flops(self) -> int:
+        return 4 * self.head_dim * self.n_q_heads * self.visible_pairs()
+
+    def attention_min_bytes(self) -> int:
+        """Q read + O write, and every request's K and V context read once, bf16."""
+        ctx = sum(k for q, k in zip(self.q_lens, self.kv_lens) if q > 0)
+        return (2 * self.n_q_heads * self.total_q + 2 * self.n_kv_heads * ctx) * self.head_dim * 2
+
+
+def qwen2vl_hybrid(seed: int = 0, n_decode: int = 96, chunk: int = 512, n_chunked: int = 4) -> HybridBatch:
+    """Qwen2-VL-7B-shaped hybrid batch: n_decode decode requests whose context is a prompt drawn like
+    the prefill workload's (image log-uniform [64, 1024] + text U{32..512}) plus U{1..256} generated
+    tokens, and n_chunked prefill requests contributing one chunk each, with 0, 1, 2, ... chunks of
+    the same size already in the cache."""
+    rng = np.random.default_rng(seed + 31)
+    q_lens, kv_lens = [], []
+    for _ in range(n_decode):
+        q_lens.append(1)
+        kv_lens.append(_log_uniform_int(rng, 64, 1024) + int(rng.integers(32, 513)) + int(rng.integers(1, 257)))
+    for c in range(n_chunked):
+        q_lens.append(chunk)
+        kv_lens.append((c + 1) * chunk)
+    order = rng.permutation(len(q_lens))
+    return HybridBatch("qwen2vl_7b_hybrid", [q_lens[i] for i in order], [kv_lens[i] for i in order], 28, 4, 128, seed=seed)
+
+
+def make_paged_inputs(h: HybridBatch, spare_blocks: int = 8, value_std: float = 1.0):
+    """bf16 CPU tensors q [Nq, Hq, d], k_cache, v_cache [num_blocks, block_size, Hkv, d] (EVERY slot holds
+    a random value, so a read from a wrong page or past the context shows), and int32 block_tables
+    [B, max_blocks] taken off a shuffled free list (entries past a request's last block are -1)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(h.seed + 17)
+    rng = np.random.default_rng(h.seed + 65537)
+    bs = h.block_size
+    blocks_of = [(k + bs - 1) // bs for k in h.kv_lens]
+    num_blocks = sum(blocks_of) + spare_blocks
+    max_blocks = max(blocks_of + [1])
+    free = rng.permutation(num_blocks).tolist()
+    tables = np.full((h.batch, max_blocks), -1, dtype=np.int32)
+    for b, nb in enumerate(blocks_of):
+        for n in range(nb):
+            tables[b, n] = free.pop()
+
+    def draw(*shape):
+        return (torch.randn(shape, generator=g, dtype=torch.float32) * value_std).to(torch.bfloat16)
+
+    q = draw(h.total_q, h.n_q_heads, h.head_dim)
+    k_cache = draw(num_blocks, bs, h.n_kv_heads, h.head_dim)
+    v_cache = draw(num_blocks, bs, h.n_kv_heads, h.head_dim)
+    return q, k_cache, v_cache, tables
+
+
 def make_qkv(w: Workload, seed: Optional[int] = None):
     """bf16 CPU tensors q [N, Hq, d], k, v [N, Hkv, d]."""
     g = torch.Generator(device="cpu")
