@@ -1,8 +1,9 @@
-"""MI355X-native packed variable-length attention + paged KV-cache write (gfx950 HIP kernels
+"""MI355X-native packed variable-length attention, paged KV-cache write and attention over the paged cache (gfx950 HIP kernels
 behind a C ABI; this package is only the thin Python binding)."""
 from .binding import (  # noqa: F401
     HydraError,
     hydra_attn_build_worklist,
+    hydra_attn_paged_fwd,
     hydra_attn_varlen_fwd,
     hydra_attn_varlen_fwd_prebuilt,
     hydra_attn_workspace_bytes,

@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert names == ["hydra_attn_build_worklist", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
+    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
                      "hydra_kv_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -101,6 +101,26 @@ def test_kv_write_argument_errors(lib):
     assert _kvw(lib, ks=64) == INVALID
     assert _kvw(lib, vs=132) == INVALID
     assert _kvw(lib, total=0, k=None, v=None, kc=None, vc=None, slots=None) == 0
+
+
+def test_paged_attn_argument_errors(lib):
+    """Every error is detected on the host before any launch: the pointers here are never dereferenced."""
+    import ctypes
+
+    P = ctypes.c_void_p(0x1000)
+    f32 = ctypes.c_float
+
+    def call(q=P, out=P, stride=28 * 128, kc=P, vc=P, bt=P, mb=8, cu=P, kl=P, batch=2, total=10, mq=8, hq=28, hkv=4, d=128, bs=16, nb=64,
+             scale=0.1):
+        return lib.hydra_attn_paged_fwd(q, out, stride, kc, vc, bt, mb, cu, kl, batch, total, mq, hq, hkv, d, bs, nb, f32(scale), None)
+
+    assert call(batch=0) == 0 and call(total=0) == 0            # nothing to do: OK without a launch
+    assert call(q=None) == 1 and call(bt=None) == 1 and call(kl=None) == 1
+    assert call(q=ctypes.c_void_p(0x1008)) == 1                 # misaligned
+    assert call(stride=28 * 128 - 8) == 1 and call(stride=28 * 128 + 4) == 1
+    assert call(hq=28, hkv=5) == 1 and call(batch=-1) == 1 and call(mq=0) == 1 and call(mb=0) == 1 and call(nb=0) == 1
+    assert call(scale=-1.0) == 1 and call(scale=float("inf")) == 1 and call(scale=float("nan")) == 1
+    assert call(d=96) == 2 and call(bs=12) == 2 and call(bs=0) == 2 and call(batch=70000) == 2
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

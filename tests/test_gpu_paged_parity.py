@@ -1,0 +1,130 @@
+"""GPU parity of attention over the paged KV cache: the HIP kernel, called through the C ABI, against
+the fp64 oracle on the same seeded bf16 inputs.  Same tolerance as the packed attention: max |diff| <=
+2e-2 and mean |diff| <= 2e-3 over all output elements."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import reference
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+def _f64(t):
+    return reference.bf16_bits_to_f64(si.bf16_bits(t))
+
+
+def _run_gpu(h, q, k_cache, v_cache, tables, scale=None, out=None, max_q_len=None):
+    import paper_2505_12658_amd as hydra
+
+    dev = torch.device("cuda:0")
+    res = hydra.hydra_attn_paged_fwd(q.to(dev), k_cache.to(dev), v_cache.to(dev), torch.from_numpy(tables).to(dev),
+                                     torch.from_numpy(h.cu_seqlens_q).to(dev), torch.tensor(h.kv_lens, dtype=torch.int32, device=dev),
+                                     max(h.max_q_len, 1) if max_q_len is None else max_q_len, h.softmax_scale if scale is None else scale,
+                                     out=out)
+    torch.cuda.synchronize()
+    return res
+
+
+def _want(h, q, k_cache, v_cache, tables, scale=None):
+    return reference.attn_paged(_f64(q), _f64(k_cache), _f64(v_cache), tables, h.cu_seqlens_q, h.kv_lens,
+                                h.softmax_scale if scale is None else scale)
+
+
+def _check(out, want):
+    got = _f64(out)
+    assert np.isfinite(got).all()
+    diff = np.abs(got - want)
+    print(f"max abs {diff.max():.3e}  mean abs {diff.mean():.3e}")
+    assert diff.max() <= MAX_ABS
+    assert diff.mean() <= MEAN_ABS
+
+
+CASES = [
+    # q_lens, kv_lens, Hq, Hkv, d, block_size
+    ([1], [1], 1, 1, 64, 16),
+    ([1, 1, 1], [1, 16, 17], 2, 1, 128, 16),
+    ([1, 0, 3, 5], [7, 4, 3, 11], 4, 2, 64, 4),
+    ([17, 64, 100, 257], [17, 64, 100, 257], 2, 2, 64, 16),           # full prefills
+    ([17, 64, 100, 257], [40, 64, 1000, 300], 2, 2, 128, 16),         # chunks at the end of longer contexts
+    ([63, 64, 65, 1, 129], [63, 128, 65, 700, 129 + 64], 7, 1, 128, 16),
+    ([1] * 9 + [200], [33, 64, 65, 127, 128, 129, 511, 512, 513, 333], 28, 4, 128, 16),
+    ([5, 130], [260, 1027], 2, 2, 80, 16),
+    ([1, 70], [2000, 70], 8, 2, 80, 32),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: f"q{'_'.join(map(str, c[0]))}-h{c[2]}k{c[3]}-d{c[4]}-b{c[5]}")
+def test_ragged_hybrid_batches_full(case):
+    q_lens, kv_lens, hq, hkv, d, bs = case
+    h = si.HybridBatch("case", q_lens, kv_lens, hq, hkv, d, block_size=bs, seed=len(q_lens) * 100 + hq)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
+def test_full_size_hybrid_batch():
+    """The benchmark's hybrid batch (96 decode requests + 4 prefill chunks of 512, 28 / 4 heads of 128), whole output."""
+    h = si.qwen2vl_hybrid()
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
+def test_matches_packed_kernel_after_cache_write():
+    """A packed causal prefill, its K/V scattered into the cache with hydra_kv_cache_write, then the paged
+    kernel over that cache: both HIP paths against the oracle of the packed attention."""
+    import paper_2505_12658_amd as hydra
+
+    dev = torch.device("cuda:0")
+    w = si.custom([100, 257, 16], 4, 2, 128, True, seed=5, kv_cache=True)
+    q, k, v = si.make_qkv(w)
+    slots, num_blocks = si.make_slot_mapping(w.lengths, 16, seed=5)
+    kc = torch.zeros((num_blocks, 16, 2, 128), dtype=torch.bfloat16, device=dev)
+    vc = torch.zeros_like(kc)
+    hydra.hydra_kv_cache_write(k.to(dev), v.to(dev), kc, vc, torch.from_numpy(slots).to(dev))
+    width = max((L + 15) // 16 for L in w.lengths)
+    tables = np.full((w.batch, width), -1, dtype=np.int32)
+    for b in range(w.batch):
+        s = int(w.cu_seqlens[b])
+        for n in range((w.lengths[b] + 15) // 16):
+            tables[b, n] = slots[s + 16 * n] // 16
+    h = si.HybridBatch("after_write", w.lengths, w.lengths, 4, 2, 128)
+    out = _run_gpu(h, q, kc, vc, tables)
+    want = reference.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, True, w.softmax_scale)
+    _check(out, want)
+
+
+def test_strided_q_canaries_and_determinism():
+    """q as a view into a wider buffer; rows of `out` that belong to no request keep their contents; two runs agree bit for bit."""
+    import paper_2505_12658_amd as hydra
+
+    dev = torch.device("cuda:0")
+    h = si.HybridBatch("views", [3, 1, 70], [19, 300, 70], 4, 2, 128, seed=9)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    wide = torch.zeros((h.total_q + 5, 4 * 128 + 64), dtype=torch.bfloat16, device=dev)
+    qv = wide[: h.total_q, 64:].view(h.total_q, 4, 128)
+    qv.copy_(q.to(dev))
+    out = torch.full((h.total_q, 4, 128), 7.0, dtype=torch.bfloat16, device=dev)
+    args = (kc.to(dev), vc.to(dev), torch.from_numpy(tables).to(dev), torch.from_numpy(h.cu_seqlens_q).to(dev),
+            torch.tensor(h.kv_lens, dtype=torch.int32, device=dev), h.max_q_len, h.softmax_scale)
+    first = hydra.hydra_attn_paged_fwd(qv, *args, out=out).clone()
+    second = hydra.hydra_attn_paged_fwd(qv, *args)
+    torch.cuda.synchronize()
+    assert torch.equal(first.view(torch.int16), second.view(torch.int16))
+    _check(first, _want(h, q, kc, vc, tables))
+    # a batch whose cu_seqlens_q stops short of the buffer: the rows after it are not written
+    short = si.HybridBatch("short", [3, 1], [19, 300], 4, 2, 128, seed=9)
+    out.fill_(7.0)
+    hydra.hydra_attn_paged_fwd(qv[:4], args[0], args[1], args[2][:2].contiguous(), torch.from_numpy(short.cu_seqlens_q).to(dev),
+                               args[4][:2].contiguous(), 3, h.softmax_scale, out=out[:4])
+    torch.cuda.synchronize()
+    assert bool((out[4:] == 7.0).all())
+
+
+def test_scale_zero_and_generous_max_q_len():
+    """softmax_scale 0 gives plain means of the visible V rows; max_q_len may exceed the batch's longest request."""
+    h = si.HybridBatch("zero", [2, 1], [40, 9], 2, 2, 64, seed=3)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables, scale=0.0, max_q_len=500), _want(h, q, kc, vc, tables, scale=0.0))
