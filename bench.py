@@ -184,6 +184,50 @@ def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode"
             "tflops_sequential": flops / seq * 1e-12, "tflops_two_streams": flops / con * 1e-12, "speedup": seq / con}
 
 
+def paged_attention(dev, n_sets: int, steps: int):
+    """Attention over the paged KV cache (hydra_attn_paged_fwd) on the hybrid batch of decode requests and
+    prefill chunks, and on its decode requests alone.  HIP events on the launch stream around every launch;
+    rotating buffer sets.  Bound: HBM (the batch's arithmetic intensity is below the ridge point)."""
+    import paper_2505_12658_amd as hydra
+
+    full = si.qwen2vl_hybrid()
+    decode_only = si.HybridBatch("qwen2vl_7b_decode_only", [q for q in full.q_lens if q == 1], [k for q, k in zip(full.q_lens, full.kv_lens) if q == 1],
+                                 full.n_q_heads, full.n_kv_heads, full.head_dim, seed=full.seed)
+    report = []
+    for h in (full, decode_only):
+        sets = []
+        for i in range(n_sets):
+            q, kc, vc, tables = si.make_paged_inputs(h)
+            sets.append((q.to(dev), kc.to(dev), vc.to(dev), torch.from_numpy(tables).to(dev), torch.empty(q.shape, dtype=torch.bfloat16, device=dev)))
+        cu = torch.from_numpy(h.cu_seqlens_q).to(dev)
+        kv_lens = torch.tensor(h.kv_lens, dtype=torch.int32, device=dev)
+
+        def launch(i):
+            q, kc, vc, tables, out = sets[i % n_sets]
+            hydra.hydra_attn_paged_fwd(q, kc, vc, tables, cu, kv_lens, h.max_q_len, h.softmax_scale, out=out)
+
+        for i in range(5):
+            launch(i)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        for i, (e0, e1) in enumerate(evs):
+            e0.record()
+            launch(i)
+            e1.record()
+        torch.cuda.synchronize()
+        t = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e-3
+        avg = float(t.mean())
+        gbs = h.attention_min_bytes() / avg * 1e-9
+        report.append({"workload": h.name, "requests": h.batch, "new_tokens": h.total_q, "context_tokens": int(sum(h.kv_lens)),
+                       "kernel": "attn_paged_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": gbs / PEAK_HBM_GBS, "avg_kernel_us": avg * 1e6, "min_kernel_us": float(t.min()) * 1e6,
+                       "algorithmic_bytes": h.attention_min_bytes(), "attention_flops": h.attention_flops(),
+                       "tflops": h.attention_flops() / avg * 1e-12})
+        del sets
+        torch.cuda.empty_cache()
+    return report
+
+
 def describe(w: si.Workload):
     return {
         "workload": w.name,
@@ -304,6 +348,8 @@ def main():
             torch.cuda.empty_cache()
         result["other_workloads"] = others
 
+    if not args.no_others:
+        result["paged_attention"] = paged_attention(dev, args.sets, max(20, args.steps // 4))
     if args.dual_stream:
         result["dual_stream"] = dual_stream(dev, args.sets, max(20, args.steps // 4))
     if not args.no_cpu_baseline:

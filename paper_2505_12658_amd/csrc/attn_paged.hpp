@@ -16,8 +16,10 @@
 // fetched while tile t is used.  Scores are kept transposed (S^T = K Q^T, O^T += V^T P^T, as in the
 // packed kernel) and the softmax is the textbook online one: running maximum and rescaling at every
 // tile.  One wave per SIMD (the 64 x D output tile plus Q take more than half of the registers).
-// This kernel is a first, plain version: no software pipelining inside the wave, and a decode row
-// occupies a whole 64-row tile.
+// Requests with few new tokens (decode steps above all) take a second form, in which the rows of ALL the
+// query heads of a KV head share one tile and the four waves split the keys: see run_packed_rows.
+// This kernel is a first, plain version: no software pipelining inside the wave, and one workgroup walks
+// a whole context (a long context in a small batch is not split over workgroups).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -57,51 +59,308 @@ struct StageGeom {
   static constexpr int kTileBytes = kKvTileRows * kRowBytes;  // one K or V tile
   static constexpr int kStageBytes = 2 * kTileBytes;          // K then V
   static constexpr int kLoadInstr = kTileBytes / 1024;
-  static constexpr int kLdsBytes = 2 * kStageBytes + 64;      // two stages; slack: D=80 reads V columns 80..95
+  // A wave's slot in the packed-rows form: its K/V stage during the loop, its unnormalised output
+  // (2 * kPvChunks * 16 registers x 64 lanes x 4 bytes) for the merge.  The wave-tile form uses the first
+  // two slots as its two stages.
+  static constexpr int kPartialBytes = 2 * kPvChunks * 16 * 64 * 4;
+  static constexpr int kSlotBytes = kStageBytes > kPartialBytes ? kStageBytes : kPartialBytes;
+  static constexpr int kLdsBytes = 4 * kSlotBytes + 64;       // slack: D=80 reads V columns 80..95
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// This wave's share of the direct-to-LDS loads of one 64-key K tile and V tile, gathered from the
-// pages.  Keys past the end of the context re-read the last valid key (always masked later).  Block
-// ids are clamped to the cache, so a corrupt table cannot make the loads leave it.
+// Direct-to-LDS loads of one 64-key K tile and V tile, gathered from the pages: load instructions
+// first, first + step, ... (a workgroup's four waves share a tile with first = wave, step = 4; a wave
+// that owns a whole tile uses first = 0, step = 1).  Keys past the end of the context re-read the last
+// valid key (always masked later).  Block ids are clamped to the cache, so a corrupt table cannot make
+// the loads leave it.
 template <int D>
-__device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const int32_t* table, unsigned char* stage, int wave, int lane,
-                                                    int kv_len, int kv_head, int kv0) {
+__device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const int32_t* table, unsigned char* stage, int first, int step,
+                                                    int lane, int kv_len, int kv_head, int kv0) {
   using G = StageGeom<D>;
-  constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
   const int64_t row_elems = (int64_t)a.n_kv_heads * D;
   const int in_block = (1 << a.block_shift) - 1;
+  for (int instr = first; instr < G::kLoadInstr; instr += step) {
+    const int flat = instr * 64 + lane;
+    const int row = flat / G::kChunks;
+    const int phys = flat % G::kChunks;
+    int tok = kv0 + row;
+    tok = tok < kv_len ? tok : kv_len - 1;
+    int block = table[tok >> a.block_shift];
+    block = block < 0 ? 0 : (block >= a.num_blocks ? a.num_blocks - 1 : block);
+    const int64_t slot = ((int64_t)block << a.block_shift) + (tok & in_block);
+    const uint16_t* kp = a.k_cache + slot * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
+    const uint16_t* vp = a.v_cache + slot * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
+    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + G::kTileBytes + instr * 1024), 16, 0, 0);
+  }
+}
+
+// A wave's state for 64 query rows (two sub-tiles of 32) and the arithmetic of one 64-key tile:
+// S^T = K Q^T, mask, online softmax (running maximum, rescaling), O^T += V^T P^T.
+template <int D>
+struct WaveTile {
+  using G = StageGeom<D>;
+  static constexpr int KS = G::kQkSteps;
+  static constexpr int CC = G::kPvChunks;
+  static constexpr int ROWB = G::kRowBytes;
+  bf16x8_t qf[2][KS];  // B operand: lane (m, hf) holds its row's columns hf*D/2 + 8*s .. +7
+  int q_lim[2];        // largest visible key index of this lane's row in sub-tile qs
+  uint32_t k_off[KS], v_off[CC];
+  f32x16_t o_acc[2][CC];
+  float row_max[2], row_sum[2];
+  float c;  // softmax_scale * log2(e)
+  int hf;
+
+  __device__ __forceinline__ void init(int lane, float scale_log2) {
+    const int m = lane & 31, sl = lane & 15, grp = (lane >> 4) & 1;
+    hf = lane >> 5;
+    c = scale_log2;
 #pragma unroll
-  for (int u = 0; u < kPerWave; ++u) {
-    const int instr = wave + 4 * u;
-    if (instr < G::kLoadInstr) {
-      const int flat = instr * 64 + lane;
-      const int row = flat / G::kChunks;
-      const int phys = flat % G::kChunks;
-      int tok = kv0 + row;
-      tok = tok < kv_len ? tok : kv_len - 1;
-      int block = table[tok >> a.block_shift];
-      block = block < 0 ? 0 : (block >= a.num_blocks ? a.num_blocks - 1 : block);
-      const int64_t slot = ((int64_t)block << a.block_shift) + (tok & in_block);
-      const uint16_t* kp = a.k_cache + slot * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
-      const uint16_t* vp = a.v_cache + slot * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + G::kTileBytes + instr * 1024), 16, 0, 0);
+    for (int s = 0; s < KS; ++s) k_off[s] = m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;
+    const int r = 4 * hf + (sl >> 2);
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc) {
+      const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
+      v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
+    }
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      row_max[qs] = -3.0e38f;
+      row_sum[qs] = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+        for (int r2 = 0; r2 < 16; ++r2) o_acc[qs][cc][r2] = 0.f;
     }
   }
+  // row pointer: this lane's query row of sub-tile qs (columns 0 .. D-1 contiguous)
+  __device__ __forceinline__ void load_q(int qs, const uint16_t* row_ptr, int limit) {
+    q_lim[qs] = limit;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[qs][s] = *reinterpret_cast<const bf16x8_t*>(row_ptr + hf * (D / 2) + 8 * s);
+  }
+
+  // one K/V tile whose first key is kv0, already complete in `stage`; need_mask: some key of the tile
+  // lies past some row's limit
+  __device__ __forceinline__ void tile(const unsigned char* stage, int kv0, bool need_mask) {
+    // ---- S^T = K Q^T ----
+    f32x16_t s_acc[2][2];  // [rb][qs]
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
+#pragma unroll
+        for (int qs = 0; qs < 2; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
+      }
+    }
+    if (need_mask) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs)
+            if (key > q_lim[qs]) s_acc[rb][qs][r] = -__builtin_inff();
+        }
+    }
+    // ---- online softmax, P in bf16 ----
+    bf16x8_t p_frag[2][2][2];  // [qs][rb][s2]
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      float tmax = s_acc[0][qs][0];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[rb][qs][r]);
+      tmax = max_with_other_half(tmax);
+      // (a row whose keys are all masked so far keeps the initial, very negative maximum: every
+      // exponential below is then exp2(-inf) = 0)
+      const float m_new = fmaxf(row_max[qs], tmax);
+      const float alpha = fast_exp2((row_max[qs] - m_new) * c);
+      row_max[qs] = m_new;
+      const float mc = m_new * c;
+      float psum = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s_acc[rb][qs][r], c, -mc));
+        if (need_mask) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+            if (key > q_lim[qs]) p[r] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) psum += p[r];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            f32x2_t pr = {p[8 * s2 + e], p[8 * s2 + e + 1]};
+            bf16x2_t pb = __builtin_convertvector(pr, bf16x2_t);
+            p_frag[qs][rb][s2][e] = pb[0];
+            p_frag[qs][rb][s2][e + 1] = pb[1];
+          }
+      }
+      row_sum[qs] = row_sum[qs] * alpha + psum;
+#pragma unroll
+      for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] *= alpha;
+    }
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const unsigned char* vp = stage + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
+          typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, both);
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
+        }
+  }
+
+  // normalise this lane's row of sub-tile qs, round to bf16 and store it at out_row (D contiguous elements)
+  __device__ __forceinline__ void store_row(int qs, uint16_t* out_row) {
+    const float total = sum_with_other_half(row_sum[qs]);
+    const float inv = 1.0f / total;
+    if (out_row == nullptr) return;  // (every lane takes part in the exchange above)
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = 32 * cc + 8 * g4 + 4 * hf;
+        if (col < D) {
+          f32x2_t a0 = {o_acc[qs][cc][4 * g4] * inv, o_acc[qs][cc][4 * g4 + 1] * inv};
+          f32x2_t a1 = {o_acc[qs][cc][4 * g4 + 2] * inv, o_acc[qs][cc][4 * g4 + 3] * inv};
+          const bf16x2_t b0 = __builtin_convertvector(a0, bf16x2_t);
+          const bf16x2_t b1 = __builtin_convertvector(a1, bf16x2_t);
+          u32x2_t pk = {__builtin_bit_cast(uint32_t, b0), __builtin_bit_cast(uint32_t, b1)};
+          *reinterpret_cast<u32x2_t*>(out_row + col) = pk;
+        }
+      }
+  }
+};
+
+// Few new tokens (q_len * group <= 64: decode steps, short chunks): ALL (token, head) pairs of one
+// (request, KV head) form one tile of rows, row = token * group + head_in_group, and the four waves
+// split the KEYS instead of the rows: wave w takes K/V tiles w, w + 4, ... into a stage of its own (no
+// workgroup barrier inside the loop, four tiles in flight per workgroup), and the four partial results
+// (maximum, sum, unnormalised output per row) are merged through LDS at the end.
+template <int D>
+__device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned char* smem, float* s_stats, const int32_t* table, int64_t q_start,
+                                                int q_len, int kv_len, int kv_head) {
+  using G = StageGeom<D>;
+  using W = WaveTile<D>;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 31;
+  const int shift = kv_len - q_len;
+  const int n_rows = q_len * a.group;
+
+  W w;
+  w.init(lane, a.scale_log2);
+  int token[2], head[2];
+  bool valid[2];
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    int r = 32 * qs + m;
+    valid[qs] = r < n_rows;
+    r = valid[qs] ? r : n_rows - 1;
+    token[qs] = r / a.group;
+    head[qs] = kv_head * a.group + (r - token[qs] * a.group);
+    w.load_q(qs, a.q + (q_start + token[qs]) * a.q_stride + head[qs] * D, shift + token[qs]);
+  }
+  unsigned char* stage = smem + wave * G::kSlotBytes;
+  const int n_tiles = (kv_len + kKvTileRows - 1) / kKvTileRows;
+  for (int t = wave; t < n_tiles; t += kWavesPerGroup) {
+    const int kv0 = t * kKvTileRows;
+    issue_kv_tile_loads<D>(a, table, stage, 0, 1, lane, kv_len, kv_head, kv0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    w.tile(stage, kv0, kv0 + kKvTileRows - 1 > shift);
+  }
+
+  // ---- merge the four waves' partial results ----
+  // statistics: s_stats[(wave * 2 + qs) * 64 + lane] = maximum, then the sums 512 floats further on
+  // (the maximum is the same in both lanes of a row, the sum is the lane's half)
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    s_stats[(wave * 2 + qs) * 64 + lane] = w.row_max[qs];
+    s_stats[512 + (wave * 2 + qs) * 64 + lane] = w.row_sum[qs];
+  }
+  // unnormalised outputs, register by register, lane-major, into the wave's own slot
+  float* mine = reinterpret_cast<float*>(stage);
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int cc = 0; cc < W::CC; ++cc)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mine[((qs * W::CC + cc) * 16 + r) * 64 + lane] = w.o_acc[qs][cc][r];
+  __syncthreads();
+  float scale_of[2][kWavesPerGroup];
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    float top = s_stats[qs * 64 + lane];
+#pragma unroll
+    for (int o = 1; o < kWavesPerGroup; ++o) top = fmaxf(top, s_stats[(o * 2 + qs) * 64 + lane]);
+    float total = 0.f;
+#pragma unroll
+    for (int o = 0; o < kWavesPerGroup; ++o) {
+      // (a wave that saw no tile, or only masked keys for this row, still holds the initial maximum: weight 0)
+      scale_of[qs][o] = fast_exp2((s_stats[(o * 2 + qs) * 64 + lane] - top) * w.c);
+      total += scale_of[qs][o] * s_stats[512 + (o * 2 + qs) * 64 + lane];
+    }
+    w.row_sum[qs] = total;
+  }
+  // wave 0 adds up the outputs and stores them
+  if (wave != 0) return;
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int cc = 0; cc < W::CC; ++cc) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float acc = w.o_acc[qs][cc][r] * scale_of[qs][0];
+#pragma unroll
+        for (int o = 1; o < kWavesPerGroup; ++o)
+          acc += scale_of[qs][o] * reinterpret_cast<const float*>(smem + o * G::kSlotBytes)[((qs * W::CC + cc) * 16 + r) * 64 + lane];
+        w.o_acc[qs][cc][r] = acc;
+      }
+      HYDRA_SCHED_FENCE();  // (one block of 16 registers at a time: the reads of all blocks at once do not fit the register file)
+    }
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+    w.store_row(qs, valid[qs] ? a.out + ((q_start + token[qs]) * a.n_q_heads + head[qs]) * D : nullptr);
 }
 #endif  // __HIP_DEVICE_COMPILE__
 
-// grid = (ceil(ceil(max_q_len / 64) * group / 4), n_kv_heads, batch): workgroup (x, y, z) takes wave tiles
-// 4x .. 4x + 3 of request z and KV head y, and leaves at once when the request has fewer.
+// grid = (1 + ceil(ceil(max_q_len / 64) * group / 4), n_kv_heads, batch).  For request z and KV head y:
+//   - q_len * group <= 64 (decode steps, short chunks): workgroup x = gridDim.x - 1 does the whole request in
+//     the packed-rows form, the others leave at once;
+//   - otherwise workgroup x takes wave tiles 4x .. 4x + 3 in the wave-tile form, and leaves at once when the
+//     request has fewer.
+// Both forms live in one kernel so that the decode requests and the prefill chunks of a batch run side by
+// side on the chip.
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_paged_kernel(const PagedArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using G = StageGeom<D>;
-  constexpr int KS = G::kQkSteps;
-  constexpr int CC = G::kPvChunks;
-  constexpr int ROWB = G::kRowBytes;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
+  __shared__ float s_stats[2 * kWavesPerGroup * 2 * 64];
 
   const int b = blockIdx.z, kv_head = blockIdx.y, f0 = blockIdx.x * kWavesPerGroup;
   const int64_t q_start = a.cu_seqlens_q[b];
@@ -113,15 +372,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (kv_len > table_keys) kv_len = (int)table_keys;
   }
   if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
+  const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
+  if (q_len * a.group <= kRows) {
+    if (blockIdx.x == gridDim.x - 1) run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
+    return;
+  }
   const int n_tok_tiles = (q_len + kRows - 1) / kRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
   if (f0 >= n_wave_tiles) return;
-  const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
   const int shift = kv_len - q_len;  // keys that precede the first new token
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
+  const int m = lane & 31;
 
   // this wave's tile
   int f = f0 + wave;
@@ -137,176 +400,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int tiles_wave = active ? (keys_of_tile(q0) + kKvTileRows - 1) / kKvTileRows : 0;
 
   // first K/V tile in flight before anything else
-  issue_kv_tile_loads<D>(a, table, smem, wave, lane, kv_len, kv_head, 0);
+  issue_kv_tile_loads<D>(a, table, smem, wave, kWavesPerGroup, lane, kv_len, kv_head, 0);
 
-  // Q fragments (B operand): lane (m, hf) holds new token q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7
-  bf16x8_t qf[2][KS];
-  int q_lim[2];  // largest visible key index for this lane's token of sub-tile qs
+  WaveTile<D> w;
+  w.init(lane, a.scale_log2);
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     int row = q0 + 32 * qs + m;
     row = row < q_len ? row : q_len - 1;
-    q_lim[qs] = shift + row;
-    const uint16_t* qp = a.q + (q_start + row) * a.q_stride + head * D + hf * (D / 2);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) qf[qs][s] = *reinterpret_cast<const bf16x8_t*>(qp + 8 * s);
+    w.load_q(qs, a.q + (q_start + row) * a.q_stride + head * D, shift + row);
   }
-
-  // LDS read offsets inside a stage
-  uint32_t k_off[KS], v_off[CC];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) k_off[s] = m * ROWB + k_swizzle<D>(m, KS * hf + s) * 16;
-  {
-    const int r = 4 * hf + (sl >> 2);
-#pragma unroll
-    for (int cc = 0; cc < CC; ++cc) {
-      const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
-      v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
-    }
-  }
-
-  f32x16_t o_acc[2][CC];
-#pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-    for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] = 0.f;
-  float row_max[2] = {-3.0e38f, -3.0e38f};
-  float row_sum[2] = {0.f, 0.f};
-  const float c = a.scale_log2;
   const int min_lim = shift + q0;  // smallest limit among the tile's tokens
 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   for (int t = 0; t < tiles_wg; ++t) {
-    unsigned char* stage = smem + (t & 1) * G::kStageBytes;
+    unsigned char* stage = smem + (t & 1) * G::kSlotBytes;
     if (t + 1 < tiles_wg)
-      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kStageBytes, wave, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
-
+      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kSlotBytes, wave, kWavesPerGroup, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
     if (t < tiles_wave) {
       const int kv0 = t * kKvTileRows;
-      // ---- S^T = K Q^T ----
-      f32x16_t s_acc[2][2];  // [rb][qs]
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-        for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
-#pragma unroll
-          for (int qs = 0; qs < 2; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
-        }
-      }
-      // ---- mask (tiles that reach past some token's limit) ----
-      const bool need_mask = kv0 + kKvTileRows - 1 > min_lim;
-      if (need_mask) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-#pragma unroll
-            for (int qs = 0; qs < 2; ++qs)
-              if (key > q_lim[qs]) s_acc[rb][qs][r] = -__builtin_inff();
-          }
-      }
-      // ---- online softmax, P in bf16 ----
-      bf16x8_t p_frag[2][2][2];  // [qs][rb][s2]
-#pragma unroll
-      for (int qs = 0; qs < 2; ++qs) {
-        float tmax = s_acc[0][qs][0];
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[rb][qs][r]);
-        tmax = max_with_other_half(tmax);
-        // (key 0 is visible to every token, so after the first tile the maximum is finite)
-        const float m_new = fmaxf(row_max[qs], tmax);
-        const float alpha = fast_exp2((row_max[qs] - m_new) * c);
-        row_max[qs] = m_new;
-        const float mc = m_new * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s_acc[rb][qs][r], c, -mc));
-          if (need_mask) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-              if (key > q_lim[qs]) p[r] = 0.f;
-            }
-          }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) psum += p[r];
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-              f32x2_t pr = {p[8 * s2 + e], p[8 * s2 + e + 1]};
-              bf16x2_t pb = __builtin_convertvector(pr, bf16x2_t);
-              p_frag[qs][rb][s2][e] = pb[0];
-              p_frag[qs][rb][s2][e + 1] = pb[1];
-            }
-        }
-        row_sum[qs] = row_sum[qs] * alpha + psum;
-#pragma unroll
-        for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] *= alpha;
-      }
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const unsigned char* vp = stage + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
-            const s16x4_t hi =
-                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
-            typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-            const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, both);
-#pragma unroll
-            for (int qs = 0; qs < 2; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
-          }
+      w.tile(stage, kv0, kv0 + kKvTileRows - 1 > min_lim);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
-  if (!active) return;
-  // ---- epilogue: normalise, round to bf16, store ----
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
-    const float total = sum_with_other_half(row_sum[qs]);
-    const float inv = 1.0f / total;
     const int row = q0 + 32 * qs + m;
-    if (row < q_len) {
-      uint16_t* op = a.out + ((q_start + row) * a.n_q_heads + head) * D;
-#pragma unroll
-      for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const int col = 32 * cc + 8 * g4 + 4 * hf;
-          if (col < D) {
-            f32x2_t a0 = {o_acc[qs][cc][4 * g4] * inv, o_acc[qs][cc][4 * g4 + 1] * inv};
-            f32x2_t a1 = {o_acc[qs][cc][4 * g4 + 2] * inv, o_acc[qs][cc][4 * g4 + 3] * inv};
-            const bf16x2_t b0 = __builtin_convertvector(a0, bf16x2_t);
-            const bf16x2_t b1 = __builtin_convertvector(a1, bf16x2_t);
-            u32x2_t pk = {__builtin_bit_cast(uint32_t, b0), __builtin_bit_cast(uint32_t, b1)};
-            *reinterpret_cast<u32x2_t*>(op + col) = pk;
-          }
-        }
-    }
+    w.store_row(qs, active && row < q_len ? a.out + ((q_start + row) * a.n_q_heads + head) * D : nullptr);
   }
 #else
   (void)a;

@@ -229,9 +229,10 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
   args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;  // (see hydra_attn_varlen_fwd_prebuilt)
 
   const int64_t tok_tiles = ((int64_t)max_q_len + hydra::paged::kRows - 1) / hydra::paged::kRows;
-  const int64_t groups = (tok_tiles * args.group + hydra::paged::kWavesPerGroup - 1) / hydra::paged::kWavesPerGroup;
-  if (groups > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)groups, (unsigned)n_kv_heads, (unsigned)batch);
+  int64_t groups = (tok_tiles * args.group + hydra::paged::kWavesPerGroup - 1) / hydra::paged::kWavesPerGroup;
+  if ((int64_t)max_q_len * args.group <= hydra::paged::kRows) groups = 0;  // every request takes the packed-rows form
+  if (groups + 1 > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)(groups + 1), (unsigned)n_kv_heads, (unsigned)batch);
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (head_dim) {
     case 64: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), 0, s, args); break;
