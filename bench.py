@@ -258,6 +258,7 @@ def main():
     ap.add_argument("--dual-stream", action="store_true",
                     help="also measure an encode workload and the prefill workload launched together on two streams "
                          "against the same two run one after the other (the paper's vision || language streams)")
+    ap.add_argument("--paged-only", action="store_true", help="only the paged-attention measurements (for profiling that kernel)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 1 GiB (fp32 x + 0 -> y): the known-size kernel that "
                          "hardware-counter readings of FETCH_SIZE / WRITE_SIZE are scaled by")
@@ -272,6 +273,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.paged_only:
+        print(json.dumps({"paged_attention": paged_attention(dev, args.sets, args.steps)}))
+        return
     w = si.WORKLOADS[args.workload]()
     batch = DeviceBatch(w, args.sets, dev)
     sec_one_stream = time_steps(batch, args.steps, args.warmup)

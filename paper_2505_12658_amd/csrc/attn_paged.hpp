@@ -79,6 +79,8 @@ __device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const in
   using G = StageGeom<D>;
   const int64_t row_elems = (int64_t)a.n_kv_heads * D;
   const int in_block = (1 << a.block_shift) - 1;
+  // (four loads at a time: the addresses of a whole tile's loads at once do not fit the register file)
+#pragma unroll 4
   for (int instr = first; instr < G::kLoadInstr; instr += step) {
     const int flat = instr * 64 + lane;
     const int row = flat / G::kChunks;
@@ -95,19 +97,19 @@ __device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const in
   }
 }
 
-// A wave's state for 64 query rows (two sub-tiles of 32) and the arithmetic of one 64-key tile:
+// A wave's state for 32 * QS query rows (QS sub-tiles of 32) and the arithmetic of one 64-key tile:
 // S^T = K Q^T, mask, online softmax (running maximum, rescaling), O^T += V^T P^T.
-template <int D>
+template <int D, int QS>
 struct WaveTile {
   using G = StageGeom<D>;
   static constexpr int KS = G::kQkSteps;
   static constexpr int CC = G::kPvChunks;
   static constexpr int ROWB = G::kRowBytes;
-  bf16x8_t qf[2][KS];  // B operand: lane (m, hf) holds its row's columns hf*D/2 + 8*s .. +7
-  int q_lim[2];        // largest visible key index of this lane's row in sub-tile qs
+  bf16x8_t qf[QS][KS];  // B operand: lane (m, hf) holds its row's columns hf*D/2 + 8*s .. +7
+  int q_lim[QS];        // largest visible key index of this lane's row in sub-tile qs
   uint32_t k_off[KS], v_off[CC];
-  f32x16_t o_acc[2][CC];
-  float row_max[2], row_sum[2];
+  f32x16_t o_acc[QS][CC];
+  float row_max[QS], row_sum[QS];
   float c;  // softmax_scale * log2(e)
   int hf;
 
@@ -124,7 +126,7 @@ struct WaveTile {
       v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
     }
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < QS; ++qs) {
       row_max[qs] = -3.0e38f;
       row_sum[qs] = 0.f;
 #pragma unroll
@@ -144,18 +146,18 @@ struct WaveTile {
   // lies past some row's limit
   __device__ __forceinline__ void tile(const unsigned char* stage, int kv0, bool need_mask) {
     // ---- S^T = K Q^T ----
-    f32x16_t s_acc[2][2];  // [rb][qs]
+    f32x16_t s_acc[2][QS];  // [rb][qs]
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
-      for (int qs = 0; qs < 2; ++qs)
+      for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
 #pragma unroll
-        for (int qs = 0; qs < 2; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
+        for (int qs = 0; qs < QS; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
       }
     }
     if (need_mask) {
@@ -165,14 +167,14 @@ struct WaveTile {
         for (int r = 0; r < 16; ++r) {
           const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
 #pragma unroll
-          for (int qs = 0; qs < 2; ++qs)
+          for (int qs = 0; qs < QS; ++qs)
             if (key > q_lim[qs]) s_acc[rb][qs][r] = -__builtin_inff();
         }
     }
     // ---- online softmax, P in bf16 ----
-    bf16x8_t p_frag[2][2][2];  // [qs][rb][s2]
+    bf16x8_t p_frag[QS][2][2];  // [qs][rb][s2]
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < QS; ++qs) {
       float tmax = s_acc[0][qs][0];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
@@ -230,7 +232,7 @@ struct WaveTile {
           const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, both);
 #pragma unroll
-          for (int qs = 0; qs < 2; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
+          for (int qs = 0; qs < QS; ++qs) o_acc[qs][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_frag[qs][rb][s2], o_acc[qs][cc], 0, 0, 0);
         }
   }
 
@@ -261,11 +263,11 @@ struct WaveTile {
 // split the KEYS instead of the rows: wave w takes K/V tiles w, w + 4, ... into a stage of its own (no
 // workgroup barrier inside the loop, four tiles in flight per workgroup), and the four partial results
 // (maximum, sum, unnormalised output per row) are merged through LDS at the end.
-template <int D>
+template <int D, int QS>
 __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned char* smem, float* s_stats, const int32_t* table, int64_t q_start,
                                                 int q_len, int kv_len, int kv_head) {
   using G = StageGeom<D>;
-  using W = WaveTile<D>;
+  using W = WaveTile<D, QS>;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 31;
@@ -274,10 +276,10 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
 
   W w;
   w.init(lane, a.scale_log2);
-  int token[2], head[2];
-  bool valid[2];
+  int token[QS], head[QS];
+  bool valid[QS];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     int r = 32 * qs + m;
     valid[qs] = r < n_rows;
     r = valid[qs] ? r : n_rows - 1;
@@ -298,22 +300,22 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   // statistics: s_stats[(wave * 2 + qs) * 64 + lane] = maximum, then the sums 512 floats further on
   // (the maximum is the same in both lanes of a row, the sum is the lane's half)
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     s_stats[(wave * 2 + qs) * 64 + lane] = w.row_max[qs];
     s_stats[512 + (wave * 2 + qs) * 64 + lane] = w.row_sum[qs];
   }
   // unnormalised outputs, register by register, lane-major, into the wave's own slot
   float* mine = reinterpret_cast<float*>(stage);
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int cc = 0; cc < W::CC; ++cc)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mine[((qs * W::CC + cc) * 16 + r) * 64 + lane] = w.o_acc[qs][cc][r];
   __syncthreads();
-  float scale_of[2][kWavesPerGroup];
+  float scale_of[QS][kWavesPerGroup];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     float top = s_stats[qs * 64 + lane];
 #pragma unroll
     for (int o = 1; o < kWavesPerGroup; ++o) top = fmaxf(top, s_stats[(o * 2 + qs) * 64 + lane]);
@@ -329,7 +331,7 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   // wave 0 adds up the outputs and stores them
   if (wave != 0) return;
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int cc = 0; cc < W::CC; ++cc) {
 #pragma unroll
@@ -343,7 +345,7 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
       HYDRA_SCHED_FENCE();  // (one block of 16 registers at a time: the reads of all blocks at once do not fit the register file)
     }
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
     w.store_row(qs, valid[qs] ? a.out + ((q_start + token[qs]) * a.n_q_heads + head[qs]) * D : nullptr);
 }
 #endif  // __HIP_DEVICE_COMPILE__
@@ -374,7 +376,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
   const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
   if (q_len * a.group <= kRows) {
-    if (blockIdx.x == gridDim.x - 1) run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
+    if (blockIdx.x == gridDim.x - 1) {
+      // (a decode step of up to 32 grouped heads needs one sub-tile of 32 rows only)
+      if (q_len * a.group <= 32) run_packed_rows<D, 1>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
+      else run_packed_rows<D, 2>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
+    }
     return;
   }
   const int n_tok_tiles = (q_len + kRows - 1) / kRows;
@@ -402,7 +408,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // first K/V tile in flight before anything else
   issue_kv_tile_loads<D>(a, table, smem, wave, kWavesPerGroup, lane, kv_len, kv_head, 0);
 
-  WaveTile<D> w;
+  WaveTile<D, 2> w;
   w.init(lane, a.scale_log2);
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
