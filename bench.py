@@ -228,6 +228,39 @@ def paged_attention(dev, n_sets: int, steps: int):
     return report
 
 
+def image_cache(dev, steps: int):
+    """Paged image cache (hydra_page_cache_write / hydra_page_cache_gather): encoder output rows into cache pages
+    and back.  HIP events around every launch; bytes = each row read once and written once + its slot."""
+    import paper_2505_12658_amd as hydra
+
+    report = []
+    for b in (si.llava15_image_cache(), si.qwen2vl_image_cache()):
+        rows = si.make_image_rows(b).to(dev)
+        slots, pages = si.make_slot_mapping(b.tokens, b.page_rows, spare_blocks=2, seed=b.seed)
+        slots = torch.from_numpy(slots).to(dev)
+        cache = torch.zeros((pages, b.page_rows, b.hidden), dtype=torch.bfloat16, device=dev)
+        out = torch.empty_like(rows)
+        entry = {"workload": b.name, "rows": b.n_rows, "row_elems": b.hidden, "page_rows": b.page_rows, "bytes": b.bytes_moved(), "bound": "hbm",
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+        for name, fn in (("write", lambda: hydra.hydra_page_cache_write(rows, cache, slots)),
+                         ("gather", lambda: hydra.hydra_page_cache_gather(cache, slots, out))):
+            for _ in range(5):
+                fn()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            torch.cuda.synchronize()
+            for e0, e1 in evs:
+                e0.record()
+                fn()
+                e1.record()
+            torch.cuda.synchronize()
+            avg = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e-3
+            entry[name] = {"avg_kernel_us": avg * 1e6, "achieved": b.bytes_moved() / avg * 1e-9, "frac": b.bytes_moved() / avg * 1e-9 / PEAK_HBM_GBS}
+        report.append(entry)
+        del rows, cache, out
+        torch.cuda.empty_cache()
+    return report
+
+
 def describe(w: si.Workload):
     return {
         "workload": w.name,
@@ -274,7 +307,7 @@ def main():
     torch.cuda.set_device(dev)
 
     if args.paged_only:
-        print(json.dumps({"paged_attention": paged_attention(dev, args.sets, args.steps)}))
+        print(json.dumps({"paged_attention": paged_attention(dev, args.sets, args.steps), "image_cache": image_cache(dev, args.steps)}))
         return
     w = si.WORKLOADS[args.workload]()
     batch = DeviceBatch(w, args.sets, dev)
@@ -354,6 +387,7 @@ def main():
 
     if not args.no_others:
         result["paged_attention"] = paged_attention(dev, args.sets, max(20, args.steps // 4))
+        result["image_cache"] = image_cache(dev, max(20, args.steps // 4))
     if args.dual_stream:
         result["dual_stream"] = dual_stream(dev, args.sets, max(20, args.steps // 4))
     if not args.no_cpu_baseline:

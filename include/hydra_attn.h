@@ -171,6 +171,33 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride,
                          int32_t block_size, int64_t num_blocks,
                          float softmax_scale, void* stream);
 
+/*
+ * Paged image cache: the vision encoder's output rows into cache pages, and back out of them.
+ *
+ * The paper keeps the image tokens that the encode stage produces in an image cache managed in pages
+ * like the KV cache (Section 5; image-cache block size 576 in Section 5.1), so that a request can move
+ * to another instance with its page table and repeated images can be reused.  The caller flattens an
+ * image's page table into one slot per row, slot = page_id * page_rows + row_in_page.
+ *
+ *   hydra_page_cache_write :  for t in [0, n_rows): s = slot_mapping[t]; if s >= 0: cache[s, :] = rows[t, :]
+ *   hydra_page_cache_gather:  for t in [0, n_rows): s = slot_mapping[t]; if s >= 0: rows[t, :] = cache[s, :]
+ *   (bit copies; rows with a negative slot are skipped; everything else keeps its contents)
+ *
+ *   rows   bf16 [n_rows, row_elems] with row stride row_stride (elements, multiple of 8, >= row_elems),
+ *          16-byte aligned: the encoder output (write) or the buffer that receives the image tokens
+ *          (gather), e.g. the image positions of the language model's input embeddings.
+ *   cache  bf16 [num_slots, row_elems], contiguous, 16-byte aligned (num_slots = pages * page_rows).
+ *   slot_mapping  device int64 [n_rows]; each value < 0 or in [0, num_slots); for the write no two rows
+ *          share a slot (otherwise undefined).
+ *   row_elems  a multiple of 8 (rows are moved in 16-byte pieces), at most 2^24.
+ *
+ * n_rows == 0 returns HYDRA_OK without launching.
+ */
+int hydra_page_cache_write(const void* rows, int64_t row_stride, void* cache, const int64_t* slot_mapping,
+                           int32_t n_rows, int32_t row_elems, int64_t num_slots, void* stream);
+int hydra_page_cache_gather(const void* cache, const int64_t* slot_mapping, void* rows, int64_t row_stride,
+                            int32_t n_rows, int32_t row_elems, int64_t num_slots, void* stream);
+
 /* Bytes of workspace hydra_attn_varlen_fwd needs for these sizes (0 if the sizes are invalid).
  * Depends only on batch, total_tokens and the head counts; pure host arithmetic. */
 size_t hydra_attn_workspace_bytes(int32_t batch, int32_t total_tokens, int32_t max_seqlen,

@@ -218,3 +218,35 @@ def kv_cache_write(k_bits, v_bits, k_cache_bits, v_cache_bits, slot_mapping, blo
         kc[blk, off] = kb[t]
         vc[blk, off] = vb[t]
     return kc, vc
+
+
+def page_cache_write(rows_bits, cache_bits, slot_mapping):
+    """Paged image cache, write direction, on raw bf16 bit patterns: returns the new cache.
+
+    The paper pages the image cache like the KV cache (Section 5; block size 576 in Section 5.1).
+    rows_bits: [n, row_elems]; cache_bits: [num_slots, row_elems] (pages flattened); slot_mapping: [n].
+    Rows are taken in order; slot < 0 skips the row; every other cache row keeps its old value."""
+    cache = np.array(cache_bits, dtype=np.uint16, copy=True)
+    rows = np.asarray(rows_bits).view(np.uint16)
+    flat = cache.reshape(-1, rows.shape[1])
+    for t, slot in enumerate(np.asarray(slot_mapping, dtype=np.int64).tolist()):
+        if slot < 0:
+            continue
+        if slot >= flat.shape[0]:
+            raise ValueError("slot out of range")
+        flat[slot] = rows[t]
+    return cache
+
+
+def page_cache_gather(cache_bits, slot_mapping, rows_bits):
+    """Paged image cache, read direction: returns the new rows (row t = cache row slot_mapping[t];
+    a row whose slot is negative keeps its old value)."""
+    rows = np.array(rows_bits, dtype=np.uint16, copy=True)
+    flat = np.asarray(cache_bits).view(np.uint16).reshape(-1, rows.shape[1])
+    for t, slot in enumerate(np.asarray(slot_mapping, dtype=np.int64).tolist()):
+        if slot < 0:
+            continue
+        if slot >= flat.shape[0]:
+            raise ValueError("slot out of range")
+        rows[t] = flat[slot]
+    return rows

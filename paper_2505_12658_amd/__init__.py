@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     hydra_attn_varlen_fwd_prebuilt,
     hydra_attn_workspace_bytes,
     hydra_kv_cache_write,
+    hydra_page_cache_gather,
+    hydra_page_cache_write,
     hydra_status_string,
     library_path,
     load_library,

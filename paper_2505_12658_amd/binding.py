@@ -46,6 +46,10 @@ def load_library() -> ctypes.CDLL:
         lib.hydra_kv_cache_write.argtypes = [vp, vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, i64, vp]
         lib.hydra_attn_paged_fwd.restype = ctypes.c_int
         lib.hydra_attn_paged_fwd.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.c_float, vp]
+        lib.hydra_page_cache_write.restype = ctypes.c_int
+        lib.hydra_page_cache_write.argtypes = [vp, i64, vp, vp, i32, i32, i64, vp]
+        lib.hydra_page_cache_gather.restype = ctypes.c_int
+        lib.hydra_page_cache_gather.argtypes = [vp, vp, vp, i64, i32, i32, i64, vp]
         lib.hydra_attn_workspace_bytes.restype = sz
         lib.hydra_attn_workspace_bytes.argtypes = [i32] * 6
         lib.hydra_status_string.restype = ctypes.c_char_p
@@ -187,3 +191,30 @@ def hydra_attn_paged_fwd(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_attn_paged_fwd")
     return out
+
+
+def _check_page_cache(rows: torch.Tensor, cache: torch.Tensor, slot_mapping: torch.Tensor):
+    if rows.dtype != torch.bfloat16 or rows.dim() != 2 or not rows.is_cuda or rows.stride(1) != 1:
+        raise TypeError("rows must be a CUDA bf16 matrix with contiguous rows")
+    if cache.dtype != torch.bfloat16 or not cache.is_cuda or not cache.is_contiguous() or cache.shape[-1] != rows.shape[1]:
+        raise TypeError("cache must be a contiguous CUDA bf16 tensor [..., row_elems]")
+    if slot_mapping.dtype != torch.int64 or not slot_mapping.is_cuda or not slot_mapping.is_contiguous() or slot_mapping.numel() != rows.shape[0]:
+        raise TypeError("slot_mapping must be a contiguous CUDA int64 tensor with one entry per row")
+
+
+def hydra_page_cache_write(rows: torch.Tensor, cache: torch.Tensor, slot_mapping: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """rows [n, row_elems] bf16 (row-strided view allowed) -> cache [pages, page_rows, row_elems] at slot_mapping (int64 [n], < 0 skips)."""
+    _check_page_cache(rows, cache, slot_mapping)
+    rc = load_library().hydra_page_cache_write(rows.data_ptr(), rows.stride(0), cache.data_ptr(), slot_mapping.data_ptr(), rows.shape[0],
+                                               rows.shape[1], cache.numel() // rows.shape[1], _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_page_cache_write")
+
+
+def hydra_page_cache_gather(cache: torch.Tensor, slot_mapping: torch.Tensor, rows: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """cache rows at slot_mapping -> rows [n, row_elems] bf16 (row-strided view allowed); rows with a negative slot keep their contents."""
+    _check_page_cache(rows, cache, slot_mapping)
+    rc = load_library().hydra_page_cache_gather(cache.data_ptr(), slot_mapping.data_ptr(), rows.data_ptr(), rows.stride(0), rows.shape[0],
+                                                rows.shape[1], cache.numel() // rows.shape[1], _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_page_cache_gather")

@@ -9,6 +9,7 @@
 #include "attn_fwd.hpp"
 #include "attn_paged.hpp"
 #include "kv_write.hpp"
+#include "page_cache.hpp"
 #include "worklist.hpp"
 
 namespace {
@@ -271,6 +272,52 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
   if (blocks > max_blocks) blocks = max_blocks;
   hipLaunchKernelGGL(hydra::kv_cache_write_kernel, dim3((unsigned)blocks), dim3(hydra::kKvWriteThreads), 0, static_cast<hipStream_t>(stream), args);
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+namespace {
+
+// Shared by the two image-cache calls: `packed` is the caller's row-major buffer (source of the write,
+// destination of the gather).
+int launch_page_cache(bool gather, const void* packed, int64_t packed_row_stride, const void* cache, const int64_t* slot_mapping,
+                      int32_t n_rows, int32_t row_elems, int64_t num_slots, void* stream) {
+  if (n_rows < 0 || row_elems <= 0 || num_slots < 0) return HYDRA_ERR_INVALID_ARG;
+  if (row_elems % 8 != 0 || row_elems > (1 << 24)) return HYDRA_ERR_UNSUPPORTED;
+  if (n_rows == 0) return HYDRA_OK;
+  if (!packed || !cache || !slot_mapping) return HYDRA_ERR_INVALID_ARG;
+  if (!aligned16(packed) || !aligned16(cache)) return HYDRA_ERR_INVALID_ARG;
+  if (packed_row_stride < row_elems || (packed_row_stride & 7)) return HYDRA_ERR_INVALID_ARG;
+  hydra::PageCacheArgs args;
+  args.slot_mapping = slot_mapping;
+  args.packed_stride16 = packed_row_stride / 8;
+  args.n_rows = n_rows;
+  args.row16 = row_elems / 8;
+  const int64_t pieces = (int64_t)n_rows * args.row16;
+  int64_t blocks = (pieces + hydra::kPageCacheThreads - 1) / hydra::kPageCacheThreads;
+  const int64_t max_blocks = 256 * 32;  // grid-stride beyond this
+  if (blocks > max_blocks) blocks = max_blocks;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (gather) {
+    args.src = static_cast<const uint4*>(cache);
+    args.dst = static_cast<uint4*>(const_cast<void*>(packed));
+    hipLaunchKernelGGL(hydra::page_cache_kernel<true>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), 0, s, args);
+  } else {
+    args.src = static_cast<const uint4*>(packed);
+    args.dst = static_cast<uint4*>(const_cast<void*>(cache));
+    hipLaunchKernelGGL(hydra::page_cache_kernel<false>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), 0, s, args);
+  }
+  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int hydra_page_cache_write(const void* rows, int64_t row_stride, void* cache, const int64_t* slot_mapping, int32_t n_rows, int32_t row_elems,
+                           int64_t num_slots, void* stream) {
+  return launch_page_cache(false, rows, row_stride, cache, slot_mapping, n_rows, row_elems, num_slots, stream);
+}
+
+int hydra_page_cache_gather(const void* cache, const int64_t* slot_mapping, void* rows, int64_t row_stride, int32_t n_rows, int32_t row_elems,
+                            int64_t num_slots, void* stream) {
+  return launch_page_cache(true, rows, row_stride, cache, slot_mapping, n_rows, row_elems, num_slots, stream);
 }
 
 }  // extern "C"

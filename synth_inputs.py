@@ -223,6 +223,45 @@ def make_paged_inputs(h: HybridBatch, spare_blocks: int = 8, value_std: float = 
     return q, k_cache, v_cache, tables
 
 
+@dataclass
+class ImageCacheBatch:
+    """Image tokens of one encode batch on their way into (or out of) the paged image cache:
+    tokens[i] rows of `hidden` bf16 values for image i, pages of `page_rows` rows (576 in the paper's
+    Section 5.1; a LLaVA-1.5 image fills exactly one page, a Qwen2-VL image a ragged number)."""
+    name: str
+    tokens: List[int]
+    hidden: int
+    page_rows: int = 576
+    seed: int = 0
+
+    @property
+    def n_rows(self) -> int:
+        return sum(self.tokens)
+
+    def bytes_moved(self) -> int:
+        """Every row read once and written once, plus the int64 slot per row."""
+        return self.n_rows * (2 * self.hidden * 2 + 8)
+
+
+def llava15_image_cache(seed: int = 0) -> ImageCacheBatch:
+    """32 LLaVA-1.5 images x 576 tokens of hidden size 4096: one full page each."""
+    return ImageCacheBatch("llava15_image_cache", [576] * 32, 4096, seed=seed)
+
+
+def qwen2vl_image_cache(seed: int = 0) -> ImageCacheBatch:
+    """32 Qwen2-VL images, tokens log-uniform in [64, 1024] (after the 2x2 merge), hidden size 3584:
+    ragged pages."""
+    rng = np.random.default_rng(seed + 11)
+    return ImageCacheBatch("qwen2vl_image_cache", [_log_uniform_int(rng, 64, 1024) for _ in range(32)], 3584, seed=seed)
+
+
+def make_image_rows(b: ImageCacheBatch):
+    """bf16 CPU tensor [n_rows, hidden], N(0,1)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(b.seed + 23)
+    return torch.randn((b.n_rows, b.hidden), generator=g, dtype=torch.float32).to(torch.bfloat16)
+
+
 def make_qkv(w: Workload, seed: Optional[int] = None):
     """bf16 CPU tensors q [N, Hq, d], k, v [N, Hkv, d]."""
     g = torch.Generator(device="cpu")

@@ -29,7 +29,7 @@ def _declared_symbols():
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
-                     "hydra_kv_cache_write", "hydra_status_string"]
+                     "hydra_kv_cache_write", "hydra_page_cache_gather", "hydra_page_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -121,6 +121,22 @@ def test_paged_attn_argument_errors(lib):
     assert call(hq=28, hkv=5) == 1 and call(batch=-1) == 1 and call(mq=0) == 1 and call(mb=0) == 1 and call(nb=0) == 1
     assert call(scale=-1.0) == 1 and call(scale=float("inf")) == 1 and call(scale=float("nan")) == 1
     assert call(d=96) == 2 and call(bs=12) == 2 and call(bs=0) == 2 and call(batch=70000) == 2
+
+
+def test_page_cache_argument_errors(lib):
+    import ctypes
+
+    P = ctypes.c_void_p(0x1000)
+    for fn, order in ((lib.hydra_page_cache_write, lambda rows, stride, cache, slots: (rows, stride, cache, slots)),
+                      (lib.hydra_page_cache_gather, lambda rows, stride, cache, slots: (cache, slots, rows, stride))):
+        def call(rows=P, stride=4096, cache=P, slots=P, n=10, row=4096, num=100):
+            return fn(*order(rows, stride, cache, slots), n, row, num, None)
+
+        assert call(n=0) == 0
+        assert call(rows=None) == 1 and call(cache=None) == 1 and call(slots=None) == 1
+        assert call(rows=ctypes.c_void_p(0x1004)) == 1 and call(stride=4088) == 1 and call(stride=4100) == 1
+        assert call(n=-1) == 1 and call(row=0) == 1
+        assert call(row=4100, stride=4104) == 2
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

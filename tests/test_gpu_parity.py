@@ -263,3 +263,36 @@ def test_kv_write_strided_and_skipped():
 @pytest.mark.parametrize("name", ["llava15_7b_prefill", "qwen2vl_7b_prefill"])
 def test_kv_write_full_size_bit_exact(name):
     _kv_case(si.WORKLOADS[name]())
+
+
+# --- paged image cache ---------------------------------------------------------------------------
+def _bits_tensor(a, dev):
+    return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+
+
+@pytest.mark.parametrize("batch", [si.ImageCacheBatch("small", [5, 0, 12, 1, 700], 64, page_rows=16), si.llava15_image_cache(), si.qwen2vl_image_cache()],
+                         ids=lambda b: b.name)
+def test_page_cache_write_and_gather_bit_exact(batch):
+    """Both directions against the oracle, bit for bit, untouched cache rows and skipped packed rows included; the
+    packed side is a row-strided view."""
+    hydra = _hydra()
+    dev = torch.device("cuda:0")
+    rows = si.make_image_rows(batch)
+    slots, pages = si.make_slot_mapping(batch.tokens, batch.page_rows, spare_blocks=3, seed=batch.seed, skip_fraction=0.02)
+    cache0 = si.make_cache_sentinel(pages, batch.page_rows, 1, batch.hidden, seed=5)[:, :, 0, :].copy()
+    wide = torch.zeros((batch.n_rows, batch.hidden + 64), dtype=torch.bfloat16, device=dev)
+    view = wide[:, 32 : 32 + batch.hidden]
+    view.copy_(rows.to(dev))
+    cache = _bits_tensor(cache0, dev)
+    slots_d = torch.from_numpy(slots).to(dev)
+    hydra.hydra_page_cache_write(view, cache, slots_d)
+    torch.cuda.synchronize()
+    want_cache = reference.page_cache_write(si.bf16_bits(rows), cache0, slots)
+    assert np.array_equal(si.bf16_bits(cache), want_cache)
+    out0 = si.make_cache_sentinel(1, batch.n_rows, 1, batch.hidden + 64, seed=6)[0, :, 0, :].copy()
+    out = _bits_tensor(out0, dev)
+    hydra.hydra_page_cache_gather(cache, slots_d, out[:, 32 : 32 + batch.hidden])
+    torch.cuda.synchronize()
+    want_out = out0.copy()
+    want_out[:, 32 : 32 + batch.hidden] = reference.page_cache_gather(want_cache, slots, out0[:, 32 : 32 + batch.hidden])
+    assert np.array_equal(si.bf16_bits(out), want_out)

@@ -323,3 +323,32 @@ def test_kv_write_oracle_gather_back_and_sentinel():
     c1, _ = reference.kv_cache_write(kbits, vbits, np.zeros((28, 16, 2, 64), np.uint16), np.zeros((28, 16, 2, 64), np.uint16),
                                      perm[: len(slots)].astype(np.int64), 16)
     assert np.array_equal(c1.reshape(-1, 2, 64)[perm], kbits)
+
+
+# --- paged image cache -----------------------------------------------------------------------
+def test_page_cache_write_then_gather_is_identity_and_leaves_the_rest():
+    rng = np.random.default_rng(21)
+    b = si.ImageCacheBatch("t", [5, 12, 1], 16, page_rows=8)
+    slots, pages = si.make_slot_mapping(b.tokens, b.page_rows, spare_blocks=2, seed=4)
+    rows = rng.integers(0, 1 << 16, size=(b.n_rows, b.hidden), dtype=np.uint16)
+    cache0 = rng.integers(0, 1 << 16, size=(pages, b.page_rows, b.hidden), dtype=np.uint16)
+    cache = reference.page_cache_write(rows, cache0, slots)
+    flat, flat0 = cache.reshape(-1, b.hidden), cache0.reshape(-1, b.hidden)
+    assert np.array_equal(flat[slots], rows)                       # every row landed in its slot
+    untouched = np.setdiff1d(np.arange(flat.shape[0]), slots)
+    assert np.array_equal(flat[untouched], flat0[untouched])      # nothing else changed
+    back = reference.page_cache_gather(cache, slots, np.zeros_like(rows))
+    assert np.array_equal(back, rows)                              # gather o write = identity
+
+
+def test_page_cache_hand_case_and_skips():
+    # two pages of two rows, rows of two values; packed rows 0..2 go to slots 3, 0 and "skip"
+    cache0 = np.array([[[1, 2], [3, 4]], [[5, 6], [7, 8]]], dtype=np.uint16)
+    rows = np.array([[10, 11], [20, 21], [30, 31]], dtype=np.uint16)
+    slots = np.array([3, 0, -1])
+    cache = reference.page_cache_write(rows, cache0, slots)
+    assert cache.tolist() == [[[20, 21], [3, 4]], [[5, 6], [10, 11]]]
+    out = reference.page_cache_gather(cache0, slots, np.array([[0, 0], [0, 0], [9, 9]], dtype=np.uint16))
+    assert out.tolist() == [[7, 8], [1, 2], [9, 9]]               # the skipped row keeps its contents
+    with pytest.raises(ValueError):
+        reference.page_cache_write(rows, cache0, np.array([4, 0, 1]))
