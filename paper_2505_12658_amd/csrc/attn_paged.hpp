@@ -9,13 +9,13 @@
 // q_len == 1 a decode step.
 //
 // Decomposition: a workgroup of 4 waves takes up to four consecutive wave tiles of one (request, KV
-// head); a wave tile is 64 new tokens of one query head, flattened as f = token_tile * group +
+// head); a wave tile is 32 new tokens of one query head, flattened as f = token_tile * group +
 // head_in_group, so with grouped queries the waves share every K/V tile.  K/V tiles of 64 keys are
 // gathered row by row from the pages (a lane looks its row's page up in the block table, then the
 // 16-byte pieces travel global -> LDS with direct-to-LDS loads) into two stages: tile t + 1 is
 // fetched while tile t is used.  Scores are kept transposed (S^T = K Q^T, O^T += V^T P^T, as in the
 // packed kernel) and the softmax is the textbook online one: running maximum and rescaling at every
-// tile.  One wave per SIMD (the 64 x D output tile plus Q take more than half of the registers).
+// tile.  Two workgroups per compute unit.
 // Requests with few new tokens (decode steps above all) take a second form, in which the rows of ALL the
 // query heads of a KV head share one tile and the four waves split the keys: see run_packed_rows.
 // This kernel is a first, plain version: no software pipelining inside the wave, and one workgroup walks
@@ -29,7 +29,7 @@
 namespace hydra {
 namespace paged {
 
-constexpr int kRows = 64;          // new tokens per wave tile
+constexpr int kRows = 32;          // new tokens (or packed rows) per wave tile
 constexpr int kWavesPerGroup = 4;  // wave tiles per workgroup
 
 struct PagedArgs {
@@ -59,29 +59,32 @@ struct StageGeom {
   static constexpr int kTileBytes = kKvTileRows * kRowBytes;  // one K or V tile
   static constexpr int kStageBytes = 2 * kTileBytes;          // K then V
   static constexpr int kLoadInstr = kTileBytes / 1024;
-  // A wave's slot in the packed-rows form: its K/V stage during the loop, its unnormalised output
-  // (2 * kPvChunks * 16 registers x 64 lanes x 4 bytes) for the merge.  The wave-tile form uses the first
-  // two slots as its two stages.
-  static constexpr int kPartialBytes = 2 * kPvChunks * 16 * 64 * 4;
-  static constexpr int kSlotBytes = kStageBytes > kPartialBytes ? kStageBytes : kPartialBytes;
-  static constexpr int kLdsBytes = 4 * kSlotBytes + 64;       // slack: D=80 reads V columns 80..95
+  // A wave's slot in the packed-rows form: a stage of a HALF tile (32 keys of K, then of V) during the loop,
+  // its unnormalised output (kPvChunks * 16 registers x 64 lanes x 4 bytes) for the merge.  Four slots; the
+  // wave-tile form uses the same memory as its two 64-key stages.
+  static constexpr int kHalfStageBytes = kStageBytes / 2;
+  static constexpr int kPartialBytes = kPvChunks * 16 * 64 * 4;
+  static constexpr int kSlotBytes = kHalfStageBytes > kPartialBytes ? kHalfStageBytes : kPartialBytes;
+  static constexpr int kLdsBytes = (4 * kSlotBytes > 2 * kStageBytes ? 4 * kSlotBytes : 2 * kStageBytes) + 64;  // slack: D=80 reads V columns 80..95
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Direct-to-LDS loads of one 64-key K tile and V tile, gathered from the pages: load instructions
+// Direct-to-LDS loads of one K tile and V tile of KEYS keys (64, or 32 for a half tile), gathered from the pages: load instructions
 // first, first + step, ... (a workgroup's four waves share a tile with first = wave, step = 4; a wave
 // that owns a whole tile uses first = 0, step = 1).  Keys past the end of the context re-read the last
 // valid key (always masked later).  Block ids are clamped to the cache, so a corrupt table cannot make
 // the loads leave it.
-template <int D>
+template <int D, int KEYS = kKvTileRows>
 __device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const int32_t* table, unsigned char* stage, int first, int step,
                                                     int lane, int kv_len, int kv_head, int kv0) {
   using G = StageGeom<D>;
+  constexpr int kTileBytes = KEYS * G::kRowBytes;  // the K rows, then the V rows
+  constexpr int kLoadInstr = kTileBytes / 1024;
   const int64_t row_elems = (int64_t)a.n_kv_heads * D;
   const int in_block = (1 << a.block_shift) - 1;
   // (four loads at a time: the addresses of a whole tile's loads at once do not fit the register file)
 #pragma unroll 4
-  for (int instr = first; instr < G::kLoadInstr; instr += step) {
+  for (int instr = first; instr < kLoadInstr; instr += step) {
     const int flat = instr * 64 + lane;
     const int row = flat / G::kChunks;
     const int phys = flat % G::kChunks;
@@ -93,7 +96,7 @@ __device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const in
     const uint16_t* kp = a.k_cache + slot * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
     const uint16_t* vp = a.v_cache + slot * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
     __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + G::kTileBytes + instr * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + kTileBytes + instr * 1024), 16, 0, 0);
   }
 }
 
@@ -123,7 +126,7 @@ struct WaveTile {
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc) {
       const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
-      v_off[cc] = G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
+      v_off[cc] = r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);  // inside the V rows of a stage
     }
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
@@ -142,13 +145,14 @@ struct WaveTile {
     for (int s = 0; s < KS; ++s) qf[qs][s] = *reinterpret_cast<const bf16x8_t*>(row_ptr + hf * (D / 2) + 8 * s);
   }
 
-  // one K/V tile whose first key is kv0, already complete in `stage`; need_mask: some key of the tile
-  // lies past some row's limit
+  // one K/V tile of 32 * RBN keys whose first key is kv0, already complete in `stage` (K rows, then V rows);
+  // need_mask: some key of the tile lies past some row's limit
+  template <int RBN = 2>
   __device__ __forceinline__ void tile(const unsigned char* stage, int kv0, bool need_mask) {
     // ---- S^T = K Q^T ----
-    f32x16_t s_acc[2][QS];  // [rb][qs]
+    f32x16_t s_acc[RBN][QS];  // [rb][qs]
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RBN; ++rb) {
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
@@ -162,7 +166,7 @@ struct WaveTile {
     }
     if (need_mask) {
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kv0 + 32 * rb + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -172,12 +176,12 @@ struct WaveTile {
         }
     }
     // ---- online softmax, P in bf16 ----
-    bf16x8_t p_frag[QS][2][2];  // [qs][rb][s2]
+    bf16x8_t p_frag[QS][RBN][2];  // [qs][rb][s2]
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
       float tmax = s_acc[0][qs][0];
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[rb][qs][r]);
       tmax = max_with_other_half(tmax);
@@ -189,7 +193,7 @@ struct WaveTile {
       const float mc = m_new * c;
       float psum = 0.f;
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < RBN; ++rb) {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s_acc[rb][qs][r], c, -mc));
@@ -222,10 +226,10 @@ struct WaveTile {
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const unsigned char* vp = stage + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
+          const unsigned char* vp = stage + RBN * 32 * ROWB + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
           const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
           const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
           typedef __attribute__((ext_vector_type(8))) short s16x8_t;
@@ -258,16 +262,17 @@ struct WaveTile {
   }
 };
 
-// Few new tokens (q_len * group <= 64: decode steps, short chunks): ALL (token, head) pairs of one
-// (request, KV head) form one tile of rows, row = token * group + head_in_group, and the four waves
-// split the KEYS instead of the rows: wave w takes K/V tiles w, w + 4, ... into a stage of its own (no
-// workgroup barrier inside the loop, four tiles in flight per workgroup), and the four partial results
+// Few new tokens (q_len * group <= 32: decode steps above all): ALL (token, head) pairs of one (request, KV
+// head) form one tile of rows, row = token * group + head_in_group, and the four waves split the KEYS
+// instead of the rows: wave w takes the half tiles (32 keys) w, w + 4, ... into a stage of its own (no
+// workgroup barrier inside the loop, four loads in flight per workgroup), and the four partial results
 // (maximum, sum, unnormalised output per row) are merged through LDS at the end.
-template <int D, int QS>
+template <int D>
 __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned char* smem, float* s_stats, const int32_t* table, int64_t q_start,
                                                 int q_len, int kv_len, int kv_head) {
   using G = StageGeom<D>;
-  using W = WaveTile<D, QS>;
+  using W = WaveTile<D, 1>;
+  constexpr int kHalfKeys = kKvTileRows / 2;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 31;
@@ -276,93 +281,78 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
 
   W w;
   w.init(lane, a.scale_log2);
-  int token[QS], head[QS];
-  bool valid[QS];
-#pragma unroll
-  for (int qs = 0; qs < QS; ++qs) {
-    int r = 32 * qs + m;
-    valid[qs] = r < n_rows;
-    r = valid[qs] ? r : n_rows - 1;
-    token[qs] = r / a.group;
-    head[qs] = kv_head * a.group + (r - token[qs] * a.group);
-    w.load_q(qs, a.q + (q_start + token[qs]) * a.q_stride + head[qs] * D, shift + token[qs]);
-  }
+  int r = m;
+  const bool valid = r < n_rows;
+  r = valid ? r : n_rows - 1;
+  const int token = r / a.group;
+  const int head = kv_head * a.group + (r - token * a.group);
+  w.load_q(0, a.q + (q_start + token) * a.q_stride + head * D, shift + token);
+
   unsigned char* stage = smem + wave * G::kSlotBytes;
-  const int n_tiles = (kv_len + kKvTileRows - 1) / kKvTileRows;
-  for (int t = wave; t < n_tiles; t += kWavesPerGroup) {
-    const int kv0 = t * kKvTileRows;
-    issue_kv_tile_loads<D>(a, table, stage, 0, 1, lane, kv_len, kv_head, kv0);
+  const int n_halves = (kv_len + kHalfKeys - 1) / kHalfKeys;
+  for (int h = wave; h < n_halves; h += kWavesPerGroup) {
+    const int kv0 = h * kHalfKeys;
+    issue_kv_tile_loads<D, kHalfKeys>(a, table, stage, 0, 1, lane, kv_len, kv_head, kv0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    w.tile(stage, kv0, kv0 + kKvTileRows - 1 > shift);
+    w.template tile<1>(stage, kv0, kv0 + kHalfKeys - 1 > shift);
   }
 
   // ---- merge the four waves' partial results ----
-  // statistics: s_stats[(wave * 2 + qs) * 64 + lane] = maximum, then the sums 512 floats further on
-  // (the maximum is the same in both lanes of a row, the sum is the lane's half)
-#pragma unroll
-  for (int qs = 0; qs < QS; ++qs) {
-    s_stats[(wave * 2 + qs) * 64 + lane] = w.row_max[qs];
-    s_stats[512 + (wave * 2 + qs) * 64 + lane] = w.row_sum[qs];
-  }
+  // statistics: s_stats[wave * 64 + lane] = maximum, the sums 256 floats further on (the maximum is the same
+  // in both lanes of a row, the sum is the lane's half)
+  s_stats[wave * 64 + lane] = w.row_max[0];
+  s_stats[256 + wave * 64 + lane] = w.row_sum[0];
   // unnormalised outputs, register by register, lane-major, into the wave's own slot
   float* mine = reinterpret_cast<float*>(stage);
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
+  for (int cc = 0; cc < W::CC; ++cc)
 #pragma unroll
-    for (int cc = 0; cc < W::CC; ++cc)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mine[((qs * W::CC + cc) * 16 + r) * 64 + lane] = w.o_acc[qs][cc][r];
+    for (int i = 0; i < 16; ++i) mine[(cc * 16 + i) * 64 + lane] = w.o_acc[0][cc][i];
   __syncthreads();
-  float scale_of[QS][kWavesPerGroup];
+  if (wave != 0) return;
+  float scale_of[kWavesPerGroup];
+  {
+    float top = s_stats[lane];
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs) {
-    float top = s_stats[qs * 64 + lane];
-#pragma unroll
-    for (int o = 1; o < kWavesPerGroup; ++o) top = fmaxf(top, s_stats[(o * 2 + qs) * 64 + lane]);
+    for (int o = 1; o < kWavesPerGroup; ++o) top = fmaxf(top, s_stats[o * 64 + lane]);
     float total = 0.f;
 #pragma unroll
     for (int o = 0; o < kWavesPerGroup; ++o) {
-      // (a wave that saw no tile, or only masked keys for this row, still holds the initial maximum: weight 0)
-      scale_of[qs][o] = fast_exp2((s_stats[(o * 2 + qs) * 64 + lane] - top) * w.c);
-      total += scale_of[qs][o] * s_stats[512 + (o * 2 + qs) * 64 + lane];
+      // (a wave that saw no key of this row still holds the initial maximum: weight 0)
+      scale_of[o] = fast_exp2((s_stats[o * 64 + lane] - top) * w.c);
+      total += scale_of[o] * s_stats[256 + o * 64 + lane];
     }
-    w.row_sum[qs] = total;
+    w.row_sum[0] = total;
   }
-  // wave 0 adds up the outputs and stores them
-  if (wave != 0) return;
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
+  for (int cc = 0; cc < W::CC; ++cc)
 #pragma unroll
-    for (int cc = 0; cc < W::CC; ++cc) {
+    for (int i = 0; i < 16; ++i) {
+      float acc = w.o_acc[0][cc][i] * scale_of[0];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float acc = w.o_acc[qs][cc][r] * scale_of[qs][0];
-#pragma unroll
-        for (int o = 1; o < kWavesPerGroup; ++o)
-          acc += scale_of[qs][o] * reinterpret_cast<const float*>(smem + o * G::kSlotBytes)[((qs * W::CC + cc) * 16 + r) * 64 + lane];
-        w.o_acc[qs][cc][r] = acc;
-      }
-      HYDRA_SCHED_FENCE();  // (one block of 16 registers at a time: the reads of all blocks at once do not fit the register file)
+      for (int o = 1; o < kWavesPerGroup; ++o)
+        acc += scale_of[o] * reinterpret_cast<const float*>(smem + o * G::kSlotBytes)[(cc * 16 + i) * 64 + lane];
+      w.o_acc[0][cc][i] = acc;
     }
-#pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
-    w.store_row(qs, valid[qs] ? a.out + ((q_start + token[qs]) * a.n_q_heads + head[qs]) * D : nullptr);
+  w.store_row(0, valid ? a.out + ((q_start + token) * a.n_q_heads + head) * D : nullptr);
 }
+
 #endif  // __HIP_DEVICE_COMPILE__
 
-// grid = (1 + ceil(ceil(max_q_len / 64) * group / 4), n_kv_heads, batch).  For request z and KV head y:
-//   - q_len * group <= 64 (decode steps, short chunks): workgroup x = gridDim.x - 1 does the whole request in
-//     the packed-rows form, the others leave at once;
+// grid = (1 + ceil(ceil(max_q_len / 32) * group / 4), n_kv_heads, batch).  For request z and KV head y:
+//   - q_len * group <= 32 (decode steps, chunks of a few tokens): workgroup x = gridDim.x - 1 does the whole
+//     request in the packed-rows form, the others leave at once;
 //   - otherwise workgroup x takes wave tiles 4x .. 4x + 3 in the wave-tile form, and leaves at once when the
 //     request has fewer.
 // Both forms live in one kernel so that the decode requests and the prefill chunks of a batch run side by
-// side on the chip.
+// side on the chip; two workgroups per compute unit (a wave keeps within 256 registers, a workgroup within
+// half of the LDS).
 template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_paged_kernel(const PagedArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_paged_kernel(const PagedArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using G = StageGeom<D>;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
-  __shared__ float s_stats[2 * kWavesPerGroup * 2 * 64];
+  __shared__ float s_stats[2 * kWavesPerGroup * 64];
 
   const int b = blockIdx.z, kv_head = blockIdx.y, f0 = blockIdx.x * kWavesPerGroup;
   const int64_t q_start = a.cu_seqlens_q[b];
@@ -376,11 +366,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
   const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
   if (q_len * a.group <= kRows) {
-    if (blockIdx.x == gridDim.x - 1) {
-      // (a decode step of up to 32 grouped heads needs one sub-tile of 32 rows only)
-      if (q_len * a.group <= 32) run_packed_rows<D, 1>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
-      else run_packed_rows<D, 2>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
-    }
+    if (blockIdx.x == gridDim.x - 1) run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
     return;
   }
   const int n_tok_tiles = (q_len + kRows - 1) / kRows;
@@ -400,7 +386,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int head = kv_head * a.group + (f - tok_tile * a.group);
   const int q0 = tok_tile * kRows;
   const int f_last = (f0 + kWavesPerGroup - 1 < n_wave_tiles ? f0 + kWavesPerGroup - 1 : n_wave_tiles - 1);
-  // keys visible to the last new token of a 64-token tile that starts at q: shift + min(q + 64, q_len)
+  // keys visible to the last new token of a tile that starts at q: shift + min(q + 32, q_len)
   auto keys_of_tile = [&](int q) { return shift + (q + kRows < q_len ? q + kRows : q_len); };
   const int tiles_wg = (keys_of_tile((f_last / a.group) * kRows) + kKvTileRows - 1) / kKvTileRows;
   const int tiles_wave = active ? (keys_of_tile(q0) + kKvTileRows - 1) / kKvTileRows : 0;
@@ -408,36 +394,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // first K/V tile in flight before anything else
   issue_kv_tile_loads<D>(a, table, smem, wave, kWavesPerGroup, lane, kv_len, kv_head, 0);
 
-  WaveTile<D, 2> w;
+  WaveTile<D, 1> w;
   w.init(lane, a.scale_log2);
-#pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
-    int row = q0 + 32 * qs + m;
-    row = row < q_len ? row : q_len - 1;
-    w.load_q(qs, a.q + (q_start + row) * a.q_stride + head * D, shift + row);
-  }
+  int row = q0 + m;
+  row = row < q_len ? row : q_len - 1;
+  w.load_q(0, a.q + (q_start + row) * a.q_stride + head * D, shift + row);
   const int min_lim = shift + q0;  // smallest limit among the tile's tokens
 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   for (int t = 0; t < tiles_wg; ++t) {
-    unsigned char* stage = smem + (t & 1) * G::kSlotBytes;
+    unsigned char* stage = smem + (t & 1) * G::kStageBytes;
     if (t + 1 < tiles_wg)
-      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kSlotBytes, wave, kWavesPerGroup, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
+      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kStageBytes, wave, kWavesPerGroup, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
     if (t < tiles_wave) {
       const int kv0 = t * kKvTileRows;
-      w.tile(stage, kv0, kv0 + kKvTileRows - 1 > min_lim);
+      w.template tile<2>(stage, kv0, kv0 + kKvTileRows - 1 > min_lim);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
-
-#pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
-    const int row = q0 + 32 * qs + m;
-    w.store_row(qs, active && row < q_len ? a.out + ((q_start + row) * a.n_q_heads + head) * D : nullptr);
-  }
+  w.store_row(0, active && q0 + m < q_len ? a.out + ((q_start + q0 + m) * a.n_q_heads + head) * D : nullptr);
 #else
   (void)a;
 #endif
