@@ -186,15 +186,17 @@ def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode"
 
 def paged_attention(dev, n_sets: int, steps: int):
     """Attention over the paged KV cache (hydra_attn_paged_fwd) on the hybrid batch of decode requests and
-    prefill chunks, and on its decode requests alone.  HIP events on the launch stream around every launch;
+    prefill chunks, on its decode requests alone, and on 8 decode requests with 16 384 tokens of context each
+    (few requests, long contexts: the library splits every context over several workgroups).  HIP events on the launch stream around every launch;
     rotating buffer sets.  Bound: HBM (the batch's arithmetic intensity is below the ridge point)."""
     import paper_2505_12658_amd as hydra
 
     full = si.qwen2vl_hybrid()
     decode_only = si.HybridBatch("qwen2vl_7b_decode_only", [q for q in full.q_lens if q == 1], [k for q, k in zip(full.q_lens, full.kv_lens) if q == 1],
                                  full.n_q_heads, full.n_kv_heads, full.head_dim, seed=full.seed)
+    long_decode = si.HybridBatch("qwen2vl_7b_long_context_decode", [1] * 8, [16384] * 8, full.n_q_heads, full.n_kv_heads, full.head_dim, seed=full.seed)
     report = []
-    for h in (full, decode_only):
+    for h in (full, decode_only, long_decode):
         sets = []
         for i in range(n_sets):
             q, kc, vc, tables = si.make_paged_inputs(h)
@@ -202,9 +204,12 @@ def paged_attention(dev, n_sets: int, steps: int):
         cu = torch.from_numpy(h.cu_seqlens_q).to(dev)
         kv_lens = torch.tensor(h.kv_lens, dtype=torch.int32, device=dev)
 
+        need = hydra.hydra_attn_paged_workspace_bytes(h.batch, h.n_kv_heads, h.head_dim, sets[0][3].shape[1], h.block_size)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
         def launch(i):
             q, kc, vc, tables, out = sets[i % n_sets]
-            hydra.hydra_attn_paged_fwd(q, kc, vc, tables, cu, kv_lens, h.max_q_len, h.softmax_scale, out=out)
+            hydra.hydra_attn_paged_fwd(q, kc, vc, tables, cu, kv_lens, h.max_q_len, h.softmax_scale, out=out, workspace=ws)
 
         for i in range(5):
             launch(i)

@@ -158,7 +158,13 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
  *        with q_len == 0 (or, invalidly, kv_len < q_len) produces no output.
  *   max_q_len     upper bound on the q_len of the batch (>= 1); sizes the launch.
  *   block_size    a power of two, at least 1 (16 in the paper).   head_dim 64, 80 or 128.
- *   batch and n_kv_heads at most 65535.   No workspace is needed.
+ *   batch and n_kv_heads at most 65535.
+ *   workspace   optional device memory (16-byte aligned; may be NULL with workspace_bytes 0).  With at least
+ *        hydra_attn_paged_workspace_bytes(...) bytes, requests with few new tokens (decode steps) have their
+ *        context split over several workgroups when the batch alone would not fill the chip or contexts are
+ *        long; the partial results pass through the workspace and a second small kernel merges them.  With
+ *        less, fewer splits (or none) are used; the result is the same up to rounding.  The workspace need
+ *        not be initialised and may be reused by the next call on the same stream.
  *
  * batch == 0 or total_q == 0 returns HYDRA_OK without launching.
  */
@@ -169,7 +175,12 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride,
                          int32_t batch, int32_t total_q, int32_t max_q_len,
                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                          int32_t block_size, int64_t num_blocks,
-                         float softmax_scale, void* stream);
+                         float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace with which hydra_attn_paged_fwd splits contexts as far as it would like to for these
+ * sizes (0: it would not split, or the sizes are invalid).  Pure host arithmetic. */
+size_t hydra_attn_paged_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32_t head_dim,
+                                        int32_t max_blocks_per_seq, int32_t block_size);
 
 /*
  * Paged image cache: the vision encoder's output rows into cache pages, and back out of them.

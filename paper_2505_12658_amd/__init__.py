@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     HydraError,
     hydra_attn_build_worklist,
     hydra_attn_paged_fwd,
+    hydra_attn_paged_workspace_bytes,
     hydra_attn_varlen_fwd,
     hydra_attn_varlen_fwd_prebuilt,
     hydra_attn_workspace_bytes,

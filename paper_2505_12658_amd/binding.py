@@ -45,7 +45,9 @@ def load_library() -> ctypes.CDLL:
         lib.hydra_kv_cache_write.restype = ctypes.c_int
         lib.hydra_kv_cache_write.argtypes = [vp, vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, i64, vp]
         lib.hydra_attn_paged_fwd.restype = ctypes.c_int
-        lib.hydra_attn_paged_fwd.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.c_float, vp]
+        lib.hydra_attn_paged_fwd.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.c_float, vp, sz, vp]
+        lib.hydra_attn_paged_workspace_bytes.restype = sz
+        lib.hydra_attn_paged_workspace_bytes.argtypes = [i32] * 5
         lib.hydra_page_cache_write.restype = ctypes.c_int
         lib.hydra_page_cache_write.argtypes = [vp, i64, vp, vp, i32, i32, i64, vp]
         lib.hydra_page_cache_gather.restype = ctypes.c_int
@@ -64,6 +66,10 @@ def hydra_status_string(status: int) -> str:
 
 def hydra_attn_workspace_bytes(batch: int, total_tokens: int, max_seqlen: int, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:
     return int(load_library().hydra_attn_workspace_bytes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim))
+
+
+def hydra_attn_paged_workspace_bytes(batch: int, n_kv_heads: int, head_dim: int, max_blocks_per_seq: int, block_size: int) -> int:
+    return int(load_library().hydra_attn_paged_workspace_bytes(batch, n_kv_heads, head_dim, max_blocks_per_seq, block_size))
 
 
 def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
@@ -165,9 +171,12 @@ def hydra_kv_cache_write(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor
 
 def hydra_attn_paged_fwd(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
                          cu_seqlens_q: torch.Tensor, kv_lens: torch.Tensor, max_q_len: int, softmax_scale: float,
-                         out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                         out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, use_workspace: bool = True,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """q [Nq, Hq, d] bf16 (new tokens of all requests, packed); caches [num_blocks, block_size, Hkv, d] bf16 contiguous;
-    block_tables int32 [B, max_blocks_per_seq]; cu_seqlens_q int32 [B+1]; kv_lens int32 [B] (context lengths, new tokens included)."""
+    block_tables int32 [B, max_blocks_per_seq]; cu_seqlens_q int32 [B+1]; kv_lens int32 [B] (context lengths, new tokens included).
+    workspace: uint8 tensor for the split of decode contexts over workgroups (allocated at the size the library asks for when
+    None and use_workspace; use_workspace=False runs without splitting)."""
     lib = load_library()
     _check_token_major(q, "q")
     if k_cache.dim() != 4 or not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape:
@@ -185,9 +194,14 @@ def hydra_attn_paged_fwd(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.
         out = torch.empty((Nq, Hq, d), dtype=torch.bfloat16, device=q.device)
     elif not out.is_contiguous() or out.shape != (Nq, Hq, d) or out.dtype != torch.bfloat16:
         raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    if workspace is None and use_workspace:
+        need = hydra_attn_paged_workspace_bytes(batch, k_cache.shape[2], d, block_tables.shape[1], k_cache.shape[1])
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need else None
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
     rc = lib.hydra_attn_paged_fwd(q.data_ptr(), out.data_ptr(), q.stride(0), k_cache.data_ptr(), v_cache.data_ptr(), block_tables.data_ptr(),
                                   block_tables.shape[1], cu_seqlens_q.data_ptr(), kv_lens.data_ptr(), batch, Nq, int(max_q_len), Hq,
-                                  k_cache.shape[2], d, k_cache.shape[1], k_cache.shape[0], float(softmax_scale), _stream_handle(stream))
+                                  k_cache.shape[2], d, k_cache.shape[1], k_cache.shape[0], float(softmax_scale), ws_ptr, ws_bytes,
+                                  _stream_handle(stream))
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_attn_paged_fwd")
     return out

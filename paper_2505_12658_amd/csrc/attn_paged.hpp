@@ -18,8 +18,9 @@
 // tile.  Two workgroups per compute unit.
 // Requests with few new tokens (decode steps above all) take a second form, in which the rows of ALL the
 // query heads of a KV head share one tile and the four waves split the keys: see run_packed_rows.
-// This kernel is a first, plain version: no software pipelining inside the wave, and one workgroup walks
-// a whole context (a long context in a small batch is not split over workgroups).
+// When the batch is small for the chip or its contexts are long, the packed-rows form also splits a context
+// over several workgroups and a second, small kernel merges their partial results (see n_splits).
+// This kernel is a first, plain version: no software pipelining inside the wave.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -48,7 +49,26 @@ struct PagedArgs {
   int32_t n_kv_heads;
   int32_t group;     // n_q_heads / n_kv_heads
   float scale_log2;  // softmax_scale * log2(e)
+  // Packed-rows form, long contexts split over workgroups: share s of a context is its half tiles (32 keys
+  // each) [s * halves_per_split, (s + 1) * halves_per_split); n_splits workgroups per (request, KV head), one per
+  // share.  A context that fits one share is done by its first workgroup, which writes `out` itself (the
+  // others leave at once); of a longer one every non-empty share leaves a partial result in `partials`, and
+  // the combine kernel merges them.  n_splits == 1: never split.
+  int32_t n_splits;
+  int32_t halves_per_split;
+  float* partials;  // [batch, n_kv_heads, n_splits] records of kPartialFloats<D> floats
 };
+
+// One partial result of the packed-rows form: per row (32 rows) the maximum and the sum, then the
+// unnormalised output rows [32][D] (only the first q_len * group rows are written and read).
+template <int D>
+constexpr int kPartialFloats = 2 * kRows + kRows * D;
+
+// half tiles [begin, end) of share s of a context of n_halves half tiles (empty past the context's end)
+__device__ __forceinline__ void split_range(int n_halves, int per, int s, int& begin, int& end) {
+  begin = s * per < n_halves ? s * per : n_halves;
+  end = begin + per < n_halves ? begin + per : n_halves;
+}
 
 template <int D>
 struct StageGeom {
@@ -269,7 +289,7 @@ struct WaveTile {
 // (maximum, sum, unnormalised output per row) are merged through LDS at the end.
 template <int D>
 __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned char* smem, float* s_stats, const int32_t* table, int64_t q_start,
-                                                int q_len, int kv_len, int kv_head) {
+                                                int q_len, int kv_len, int kv_head, int request, int split) {
   using G = StageGeom<D>;
   using W = WaveTile<D, 1>;
   constexpr int kHalfKeys = kKvTileRows / 2;
@@ -290,7 +310,11 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
 
   unsigned char* stage = smem + wave * G::kSlotBytes;
   const int n_halves = (kv_len + kHalfKeys - 1) / kHalfKeys;
-  for (int h = wave; h < n_halves; h += kWavesPerGroup) {
+  int h_begin, h_end;
+  split_range(n_halves, a.halves_per_split, split, h_begin, h_end);
+  if (h_begin >= h_end) return;  // an empty share: the combine kernel knows and skips it
+  const bool whole = n_halves <= a.halves_per_split;  // the context fits one share: this workgroup writes the output
+  for (int h = h_begin + wave; h < h_end; h += kWavesPerGroup) {
     const int kv0 = h * kHalfKeys;
     issue_kv_tile_loads<D, kHalfKeys>(a, table, stage, 0, 1, lane, kv_len, kv_head, kv0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -334,7 +358,34 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
         acc += scale_of[o] * reinterpret_cast<const float*>(smem + o * G::kSlotBytes)[(cc * 16 + i) * 64 + lane];
       w.o_acc[0][cc][i] = acc;
     }
-  w.store_row(0, valid ? a.out + ((q_start + token) * a.n_q_heads + head) * D : nullptr);
+  if (whole) {
+    w.store_row(0, valid ? a.out + ((q_start + token) * a.n_q_heads + head) * D : nullptr);
+    return;
+  }
+  // this share's partial result: the row's maximum, its sum (both halves of the row added up) and its
+  // unnormalised output, for the combine kernel
+  const float total = sum_with_other_half(w.row_sum[0]);
+  float top = s_stats[lane];
+#pragma unroll
+  for (int o = 1; o < kWavesPerGroup; ++o) top = fmaxf(top, s_stats[o * 64 + lane]);
+  float* rec = a.partials + (((int64_t)request * a.n_kv_heads + kv_head) * a.n_splits + split) * kPartialFloats<D>;
+  if (valid) {
+    if (w.hf == 0) {
+      rec[m] = top;
+      rec[kRows + m] = total;
+    }
+    float* row = rec + 2 * kRows + m * D;
+#pragma unroll
+    for (int cc = 0; cc < W::CC; ++cc)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = 32 * cc + 8 * g4 + 4 * w.hf;
+        if (col < D) {
+          f32x4_t v = {w.o_acc[0][cc][4 * g4], w.o_acc[0][cc][4 * g4 + 1], w.o_acc[0][cc][4 * g4 + 2], w.o_acc[0][cc][4 * g4 + 3]};
+          *reinterpret_cast<f32x4_t*>(row + col) = v;
+        }
+      }
+  }
 }
 
 #endif  // __HIP_DEVICE_COMPILE__
@@ -366,12 +417,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
   const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
   if (q_len * a.group <= kRows) {
-    if (blockIdx.x == gridDim.x - 1) run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head);
+    const int first_rows_wg = (int)gridDim.x - a.n_splits;
+    if ((int)blockIdx.x >= first_rows_wg)
+      run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head, b, (int)blockIdx.x - first_rows_wg);
     return;
   }
   const int n_tok_tiles = (q_len + kRows - 1) / kRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
-  if (f0 >= n_wave_tiles) return;
+  if (f0 >= n_wave_tiles) return;  // (the last n_splits workgroups of the row belong to the packed-rows form: f0 is past every tile there)
   const int shift = kv_len - q_len;  // keys that precede the first new token
 
   const int lane = threadIdx.x & 63;
@@ -416,6 +469,78 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
   }
   w.store_row(0, active && q0 + m < q_len ? a.out + ((q_start + q0 + m) * a.n_q_heads + head) * D : nullptr);
+#else
+  (void)a;
+#endif
+}
+
+// Merges the partial results of the packed-rows form when contexts were split over workgroups
+// (n_splits > 1).  grid = (n_kv_heads, batch), 256 threads.  Requests that took the wave-tile form, have
+// no new tokens, or whose context fits one share (already finished by one workgroup) are skipped.
+// First the shares' row statistics go to LDS and every row's weights (exp2 of its maximum's distance to the
+// overall maximum, divided by the overall sum) are formed there; then every thread adds up 4 output
+// columns of one row over the shares.
+constexpr int kMaxSplits = 16;
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_paged_combine_kernel(const PagedArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __shared__ float s_max[kMaxSplits][kRows], s_weight[kMaxSplits][kRows];
+  const int b = blockIdx.y, kv_head = blockIdx.x;
+  const int64_t q_start = a.cu_seqlens_q[b];
+  const int q_len = a.cu_seqlens_q[b + 1] - (int)q_start;
+  int kv_len = a.kv_lens[b];
+  const int64_t table_keys = (int64_t)a.max_blocks_per_seq << a.block_shift;
+  if (kv_len > table_keys) kv_len = (int)table_keys;
+  if (q_len <= 0 || kv_len < q_len || q_len * a.group > kRows) return;
+  const int n_rows = q_len * a.group;
+  const int n_halves = (kv_len + kKvTileRows / 2 - 1) / (kKvTileRows / 2);
+  if (n_halves <= a.halves_per_split) return;  // done by one workgroup, which wrote the output itself
+  const int n_shares = (n_halves + a.halves_per_split - 1) / a.halves_per_split;  // the non-empty shares come first
+  const float* recs = a.partials + ((int64_t)b * a.n_kv_heads + kv_head) * a.n_splits * kPartialFloats<D>;
+  // share s, row r: maximum -> s_max, sum -> s_weight (for now)
+  for (int i = threadIdx.x; i < n_shares * kRows; i += 256) {
+    const int s = i / kRows, r = i - s * kRows;
+    const bool live = r < n_rows;
+    s_max[s][r] = live ? recs[(int64_t)s * kPartialFloats<D> + r] : 0.f;
+    s_weight[s][r] = live ? recs[(int64_t)s * kPartialFloats<D> + kRows + r] : 0.f;
+  }
+  __syncthreads();
+  if (threadIdx.x < kRows) {
+    const int r = threadIdx.x;
+    float top = s_max[0][r];
+    for (int s = 1; s < n_shares; ++s) top = fmaxf(top, s_max[s][r]);
+    float total = 0.f;
+    for (int s = 0; s < n_shares; ++s) {
+      const float w = fast_exp2((s_max[s][r] - top) * a.scale_log2);
+      total += w * s_weight[s][r];
+      s_max[s][r] = w;
+    }
+    const float inv = r < n_rows ? 1.0f / total : 0.f;
+    for (int s = 0; s < n_shares; ++s) s_weight[s][r] = s_max[s][r] * inv;
+  }
+  __syncthreads();
+  constexpr int kColGroups = D / 4;
+  for (int i = threadIdx.x; i < n_rows * kColGroups; i += 256) {
+    const int row = i / kColGroups, col = (i - row * kColGroups) * 4;
+    const float* src = recs + 2 * kRows + row * D + col;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int s = 0; s < n_shares; ++s) {
+      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(src + (int64_t)s * kPartialFloats<D>);
+      const float w = s_weight[s][row];
+      acc[0] += w * v[0];
+      acc[1] += w * v[1];
+      acc[2] += w * v[2];
+      acc[3] += w * v[3];
+    }
+    const int token = row / a.group;
+    const int head = kv_head * a.group + (row - token * a.group);
+    f32x2_t a0 = {acc[0], acc[1]}, a1 = {acc[2], acc[3]};
+    u32x2_t pk = {__builtin_bit_cast(uint32_t, __builtin_convertvector(a0, bf16x2_t)),
+                  __builtin_bit_cast(uint32_t, __builtin_convertvector(a1, bf16x2_t))};
+    *reinterpret_cast<u32x2_t*>(a.out + ((q_start + token) * a.n_q_heads + head) * D + col) = pk;
+  }
 #else
   (void)a;
 #endif

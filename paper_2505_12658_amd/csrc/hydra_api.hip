@@ -45,6 +45,26 @@ hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned comput
   return hipGetLastError();
 }
 
+// Bytes of one partial result of the paged kernel's packed-rows form.
+size_t paged_partial_bytes(int head_dim) { return (size_t)(2 * hydra::paged::kRows + hydra::paged::kRows * head_dim) * sizeof(float); }
+
+// Workgroups per (request, KV head) over which the packed-rows form of the paged kernel splits a context.
+// A function of the launch sizes alone (both the workspace-size query and the launch use it): as many as
+// fit the chip's 512 workgroup slots together (a batch that already brings 256 (request, KV head) pairs or
+// more is not split: measured, the extra workgroups and the merge then cost more than the imbalance they
+// remove), at least 512 keys per share of the longest context the block table can describe, at most 16, and
+// no more than the workspace holds.
+int paged_splits(int32_t batch, int32_t n_kv_heads, int32_t head_dim, int32_t max_blocks_per_seq, int32_t block_size, size_t workspace_bytes) {
+  const int64_t pairs = (int64_t)batch * n_kv_heads;
+  int64_t want = 512 / pairs;
+  const int64_t by_length = ((int64_t)max_blocks_per_seq * block_size) / 512;
+  if (want > by_length) want = by_length;
+  if (want > hydra::paged::kMaxSplits) want = hydra::paged::kMaxSplits;
+  const int64_t fits = (int64_t)(workspace_bytes / (paged_partial_bytes(head_dim) * (size_t)pairs));
+  if (want > fits) want = fits;
+  return want < 2 ? 1 : (int)want;
+}
+
 }  // namespace
 
 extern "C" {
@@ -196,7 +216,8 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
 int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const void* k_cache, const void* v_cache,
                          const int32_t* block_tables, int32_t max_blocks_per_seq, const int32_t* cu_seqlens_q, const int32_t* kv_lens,
                          int32_t batch, int32_t total_q, int32_t max_q_len, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                         int32_t block_size, int64_t num_blocks, float softmax_scale, void* stream) {
+                         int32_t block_size, int64_t num_blocks, float softmax_scale, void* workspace, size_t workspace_bytes,
+                         void* stream) {
   if (batch < 0 || total_q < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0) return HYDRA_ERR_INVALID_ARG;
   if (!head_dim_supported(head_dim)) return HYDRA_ERR_UNSUPPORTED;
   if (block_size < 1 || (block_size & (block_size - 1)) != 0) return HYDRA_ERR_UNSUPPORTED;
@@ -208,6 +229,7 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
   if (q_token_stride < (int64_t)n_q_heads * head_dim || (q_token_stride & 7)) return HYDRA_ERR_INVALID_ARG;
   if (batch > 65535 || n_kv_heads > 65535 || num_blocks > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
   if ((int64_t)max_blocks_per_seq * block_size > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
+  if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return HYDRA_ERR_WORKSPACE;
 
   hydra::paged::PagedArgs args;
   args.q = static_cast<const uint16_t*>(q);
@@ -232,15 +254,38 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
   const int64_t tok_tiles = ((int64_t)max_q_len + hydra::paged::kRows - 1) / hydra::paged::kRows;
   int64_t groups = (tok_tiles * args.group + hydra::paged::kWavesPerGroup - 1) / hydra::paged::kWavesPerGroup;
   if ((int64_t)max_q_len * args.group <= hydra::paged::kRows) groups = 0;  // every request takes the packed-rows form
-  if (groups + 1 > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)(groups + 1), (unsigned)n_kv_heads, (unsigned)batch);
+  const int splits = paged_splits(batch, n_kv_heads, head_dim, max_blocks_per_seq, block_size, workspace_bytes);
+  args.n_splits = splits;
+  {
+    const int64_t max_halves = ((int64_t)max_blocks_per_seq * block_size + 31) / 32;
+    args.halves_per_split = (int32_t)((max_halves + splits - 1) / splits);
+  }
+  args.partials = static_cast<float*>(workspace);
+  if (groups + splits > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)(groups + splits), (unsigned)n_kv_heads, (unsigned)batch);
+  const dim3 combine_grid((unsigned)n_kv_heads, (unsigned)batch);
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (head_dim) {
-    case 64: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), 0, s, args); break;
-    case 80: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<80>, grid, dim3(256), 0, s, args); break;
-    default: hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<128>, grid, dim3(256), 0, s, args); break;
+    case 64:
+      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), 0, s, args);
+      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<64>, combine_grid, dim3(256), 0, s, args);
+      break;
+    case 80:
+      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<80>, grid, dim3(256), 0, s, args);
+      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<80>, combine_grid, dim3(256), 0, s, args);
+      break;
+    default:
+      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<128>, grid, dim3(256), 0, s, args);
+      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<128>, combine_grid, dim3(256), 0, s, args);
+      break;
   }
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+size_t hydra_attn_paged_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32_t head_dim, int32_t max_blocks_per_seq, int32_t block_size) {
+  if (batch <= 0 || n_kv_heads <= 0 || !head_dim_supported(head_dim) || max_blocks_per_seq < 1 || block_size < 1) return 0;
+  const int splits = paged_splits(batch, n_kv_heads, head_dim, max_blocks_per_seq, block_size, ~(size_t)0);
+  return splits > 1 ? paged_partial_bytes(head_dim) * (size_t)splits * (size_t)batch * (size_t)n_kv_heads : 0;
 }
 
 int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, int64_t v_token_stride, void* k_cache, void* v_cache,

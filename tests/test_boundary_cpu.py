@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
+    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_paged_workspace_bytes", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
                      "hydra_kv_cache_write", "hydra_page_cache_gather", "hydra_page_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -111,8 +111,8 @@ def test_paged_attn_argument_errors(lib):
     f32 = ctypes.c_float
 
     def call(q=P, out=P, stride=28 * 128, kc=P, vc=P, bt=P, mb=8, cu=P, kl=P, batch=2, total=10, mq=8, hq=28, hkv=4, d=128, bs=16, nb=64,
-             scale=0.1):
-        return lib.hydra_attn_paged_fwd(q, out, stride, kc, vc, bt, mb, cu, kl, batch, total, mq, hq, hkv, d, bs, nb, f32(scale), None)
+             scale=0.1, ws=None, wsb=0):
+        return lib.hydra_attn_paged_fwd(q, out, stride, kc, vc, bt, mb, cu, kl, batch, total, mq, hq, hkv, d, bs, nb, f32(scale), ws, wsb, None)
 
     assert call(batch=0) == 0 and call(total=0) == 0            # nothing to do: OK without a launch
     assert call(q=None) == 1 and call(bt=None) == 1 and call(kl=None) == 1
@@ -121,6 +121,12 @@ def test_paged_attn_argument_errors(lib):
     assert call(hq=28, hkv=5) == 1 and call(batch=-1) == 1 and call(mq=0) == 1 and call(mb=0) == 1 and call(nb=0) == 1
     assert call(scale=-1.0) == 1 and call(scale=float("inf")) == 1 and call(scale=float("nan")) == 1
     assert call(d=96) == 2 and call(bs=12) == 2 and call(bs=0) == 2 and call(batch=70000) == 2
+    assert call(ws=None, wsb=64) == 3 and call(ws=ctypes.c_void_p(0x1004), wsb=64) == 3
+    # workspace size: nothing for a batch that fills the chip or for short contexts, something for a small batch of long contexts
+    assert lib.hydra_attn_paged_workspace_bytes(1024, 4, 128, 64, 16) == 0
+    assert lib.hydra_attn_paged_workspace_bytes(8, 4, 128, 16, 16) == 0
+    assert lib.hydra_attn_paged_workspace_bytes(8, 4, 128, 1024, 16) == 8 * 4 * 16 * (64 + 32 * 128) * 4
+    assert lib.hydra_attn_paged_workspace_bytes(0, 4, 128, 1024, 16) == 0 and lib.hydra_attn_paged_workspace_bytes(8, 4, 96, 1024, 16) == 0
 
 
 def test_page_cache_argument_errors(lib):

@@ -17,14 +17,14 @@ def _f64(t):
     return reference.bf16_bits_to_f64(si.bf16_bits(t))
 
 
-def _run_gpu(h, q, k_cache, v_cache, tables, scale=None, out=None, max_q_len=None):
+def _run_gpu(h, q, k_cache, v_cache, tables, scale=None, out=None, max_q_len=None, **kw):
     import paper_2505_12658_amd as hydra
 
     dev = torch.device("cuda:0")
     res = hydra.hydra_attn_paged_fwd(q.to(dev), k_cache.to(dev), v_cache.to(dev), torch.from_numpy(tables).to(dev),
                                      torch.from_numpy(h.cu_seqlens_q).to(dev), torch.tensor(h.kv_lens, dtype=torch.int32, device=dev),
                                      max(h.max_q_len, 1) if max_q_len is None else max_q_len, h.softmax_scale if scale is None else scale,
-                                     out=out)
+                                     out=out, **kw)
     torch.cuda.synchronize()
     return res
 
@@ -128,3 +128,30 @@ def test_scale_zero_and_generous_max_q_len():
     h = si.HybridBatch("zero", [2, 1], [40, 9], 2, 2, 64, seed=3)
     q, kc, vc, tables = si.make_paged_inputs(h)
     _check(_run_gpu(h, q, kc, vc, tables, scale=0.0, max_q_len=500), _want(h, q, kc, vc, tables, scale=0.0))
+
+
+SPLIT_CASES = [
+    # q_lens, kv_lens, Hq, Hkv, d: few requests with long contexts, so that the packed-rows form splits them over workgroups
+    ([1, 1, 1], [5000, 40, 1300], 28, 4, 128),          # shares of the short contexts are empty
+    ([4, 1], [3000, 2500], 8, 2, 64),                   # 4 tokens x 4 grouped heads = 16 packed rows, end-aligned mask inside a share
+    ([1] * 6, [8192, 100, 4097, 33, 2048, 700], 14, 2, 80),
+    ([1, 300], [6000, 900], 28, 4, 128),                # a split decode request next to a chunk in the wave-tile form
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: f"q{'_'.join(map(str, c[0]))}-kv{max(c[1])}-h{c[2]}k{c[3]}-d{c[4]}")
+def test_contexts_split_over_workgroups(case):
+    """Small batches of long contexts: with the workspace the library asks for, contexts are split over several
+    workgroups and merged by the combine kernel; without it one workgroup walks each context.  Both against the oracle."""
+    import paper_2505_12658_amd as hydra
+
+    q_lens, kv_lens, hq, hkv, d = case
+    h = si.HybridBatch("split", q_lens, kv_lens, hq, hkv, d, seed=hq + len(q_lens))
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    assert hydra.hydra_attn_paged_workspace_bytes(h.batch, hkv, d, tables.shape[1], 16) > 0
+    want = _want(h, q, kc, vc, tables)
+    _check(_run_gpu(h, q, kc, vc, tables), want)
+    _check(_run_gpu(h, q, kc, vc, tables, use_workspace=False), want)
+    # a workspace too small for the preferred number of shares still gives the right answer (fewer shares)
+    small = torch.empty(hydra.hydra_attn_paged_workspace_bytes(h.batch, hkv, d, tables.shape[1], 16) // 3, dtype=torch.uint8, device="cuda:0")
+    _check(_run_gpu(h, q, kc, vc, tables, workspace=small), want)
