@@ -89,34 +89,58 @@ struct StageGeom {
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Direct-to-LDS loads of one K tile and V tile of KEYS keys (64, or 32 for a half tile), gathered from the pages: load instructions
-// first, first + step, ... (a workgroup's four waves share a tile with first = wave, step = 4; a wave
-// that owns a whole tile uses first = 0, step = 1).  Keys past the end of the context re-read the last
-// valid key (always masked later).  Block ids are clamped to the cache, so a corrupt table cannot make
-// the loads leave it.
-template <int D, int KEYS = kKvTileRows>
-__device__ __forceinline__ void issue_kv_tile_loads(const PagedArgs& a, const int32_t* table, unsigned char* stage, int first, int step,
-                                                    int lane, int kv_len, int kv_head, int kv0) {
+// The K/V tiles are gathered from the pages in two moves, so that the block-table lookup of a tile is in
+// flight while the tile before it is fetched and used (done in one move, every tile would pay the lookup's
+// round trip before its loads can even be issued):
+//   fetch_tile_slots: per load instruction of this wave, the cache row ("slot" = block * block_size + offset)
+//     of this lane's key.  Load instructions first, first + step, ... (a workgroup's four waves share a tile
+//     with first = wave, step = 4; a wave that owns a whole tile uses first = 0, step = 1).  Keys past the end
+//     of the context re-read the last valid key (always masked later).  Block ids are clamped to the cache,
+//     so a corrupt table cannot make the loads leave it.
+//   issue_tile_loads: the direct-to-LDS loads of the K rows and V rows of those slots (KEYS keys: 64, or 32
+//     for a half tile; K rows first, then V rows).
+template <int D, int KEYS, int STEP>
+struct TileSlots {
+  static constexpr int kLoadInstr = KEYS * StageGeom<D>::kRowBytes / 1024;
+  static constexpr int kCount = (kLoadInstr + STEP - 1) / STEP;
+  int64_t slot[kCount];
+};
+
+template <int D, int KEYS, int STEP>
+__device__ __forceinline__ void fetch_tile_slots(TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, const int32_t* table, int first, int lane,
+                                                 int kv_len, int kv0) {
   using G = StageGeom<D>;
-  constexpr int kTileBytes = KEYS * G::kRowBytes;  // the K rows, then the V rows
-  constexpr int kLoadInstr = kTileBytes / 1024;
-  const int64_t row_elems = (int64_t)a.n_kv_heads * D;
   const int in_block = (1 << a.block_shift) - 1;
-  // (four loads at a time: the addresses of a whole tile's loads at once do not fit the register file)
-#pragma unroll 4
-  for (int instr = first; instr < kLoadInstr; instr += step) {
-    const int flat = instr * 64 + lane;
-    const int row = flat / G::kChunks;
-    const int phys = flat % G::kChunks;
+#pragma unroll
+  for (int u = 0; u < TileSlots<D, KEYS, STEP>::kCount; ++u) {
+    const int instr = first + STEP * u;
+    const int row = (instr * 64 + lane) / G::kChunks;
     int tok = kv0 + row;
     tok = tok < kv_len ? tok : kv_len - 1;
     int block = table[tok >> a.block_shift];
     block = block < 0 ? 0 : (block >= a.num_blocks ? a.num_blocks - 1 : block);
-    const int64_t slot = ((int64_t)block << a.block_shift) + (tok & in_block);
-    const uint16_t* kp = a.k_cache + slot * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
-    const uint16_t* vp = a.v_cache + slot * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
-    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + kTileBytes + instr * 1024), 16, 0, 0);
+    ts.slot[u] = ((int64_t)block << a.block_shift) + (tok & in_block);
+  }
+}
+
+template <int D, int KEYS, int STEP>
+__device__ __forceinline__ void issue_tile_loads(const TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, unsigned char* stage, int first, int lane,
+                                                 int kv_head) {
+  using G = StageGeom<D>;
+  constexpr int kTileBytes = KEYS * G::kRowBytes;
+  const int64_t row_elems = (int64_t)a.n_kv_heads * D;
+#pragma unroll
+  for (int u = 0; u < TileSlots<D, KEYS, STEP>::kCount; ++u) {
+    const int instr = first + STEP * u;
+    if (instr < TileSlots<D, KEYS, STEP>::kLoadInstr) {
+      const int flat = instr * 64 + lane;
+      const int row = flat / G::kChunks;
+      const int phys = flat % G::kChunks;
+      const uint16_t* kp = a.k_cache + ts.slot[u] * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
+      const uint16_t* vp = a.v_cache + ts.slot[u] * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + kTileBytes + instr * 1024), 16, 0, 0);
+    }
   }
 }
 
@@ -171,19 +195,22 @@ struct WaveTile {
   __device__ __forceinline__ void tile(const unsigned char* stage, int kv0, bool need_mask) {
     // ---- S^T = K Q^T ----
     f32x16_t s_acc[RBN][QS];  // [rb][qs]
+    // (consecutive matrix instructions go to different accumulators wherever there are several: one that
+    // continues the accumulator of the instruction right before it waits for that one to finish)
 #pragma unroll
-    for (int rb = 0; rb < RBN; ++rb) {
+    for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[rb][qs][r] = 0.f;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int rb = 0; rb < RBN; ++rb) {
         const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(stage + rb * 32 * ROWB + k_off[s]);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) s_acc[rb][qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][s], s_acc[rb][qs], 0, 0, 0);
       }
-    }
     if (need_mask) {
 #pragma unroll
       for (int rb = 0; rb < RBN; ++rb)
@@ -244,11 +271,11 @@ struct WaveTile {
     }
     // ---- O^T += V^T P^T ----
 #pragma unroll
-    for (int cc = 0; cc < CC; ++cc)
+    for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
-      for (int rb = 0; rb < RBN; ++rb)
+      for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
+        for (int cc = 0; cc < CC; ++cc) {
           const unsigned char* vp = stage + RBN * 32 * ROWB + v_off[cc] + (32 * rb + 16 * s2) * ROWB;
           const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp));
           const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_PTR(vp + 8 * ROWB));
@@ -314,11 +341,16 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   split_range(n_halves, a.halves_per_split, split, h_begin, h_end);
   if (h_begin >= h_end) return;  // an empty share: the combine kernel knows and skips it
   const bool whole = n_halves <= a.halves_per_split;  // the context fits one share: this workgroup writes the output
+  TileSlots<D, kHalfKeys, 1> slots, next_slots;
+  if (h_begin + wave < h_end) fetch_tile_slots(slots, a, table, 0, lane, kv_len, (h_begin + wave) * kHalfKeys);
   for (int h = h_begin + wave; h < h_end; h += kWavesPerGroup) {
     const int kv0 = h * kHalfKeys;
-    issue_kv_tile_loads<D, kHalfKeys>(a, table, stage, 0, 1, lane, kv_len, kv_head, kv0);
+    issue_tile_loads(slots, a, stage, 0, lane, kv_head);
+    // the next half tile's block-table lookup travels together with this one's rows
+    if (h + kWavesPerGroup < h_end) fetch_tile_slots(next_slots, a, table, 0, lane, kv_len, (h + kWavesPerGroup) * kHalfKeys);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     w.template tile<1>(stage, kv0, kv0 + kHalfKeys - 1 > shift);
+    slots = next_slots;
   }
 
   // ---- merge the four waves' partial results ----
@@ -444,8 +476,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int tiles_wg = (keys_of_tile((f_last / a.group) * kRows) + kKvTileRows - 1) / kKvTileRows;
   const int tiles_wave = active ? (keys_of_tile(q0) + kKvTileRows - 1) / kKvTileRows : 0;
 
-  // first K/V tile in flight before anything else
-  issue_kv_tile_loads<D>(a, table, smem, wave, kWavesPerGroup, lane, kv_len, kv_head, 0);
+  // first K/V tile in flight before anything else, and the second tile's block-table lookup behind it
+  TileSlots<D, kKvTileRows, kWavesPerGroup> slots, next_slots;
+  fetch_tile_slots(slots, a, table, wave, lane, kv_len, 0);
+  issue_tile_loads(slots, a, smem, wave, lane, kv_head);
+  if (1 < tiles_wg) fetch_tile_slots(slots, a, table, wave, lane, kv_len, kKvTileRows);
 
   WaveTile<D, 1> w;
   w.init(lane, a.scale_log2);
@@ -459,14 +494,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   for (int t = 0; t < tiles_wg; ++t) {
     unsigned char* stage = smem + (t & 1) * G::kStageBytes;
-    if (t + 1 < tiles_wg)
-      issue_kv_tile_loads<D>(a, table, smem + ((t + 1) & 1) * G::kStageBytes, wave, kWavesPerGroup, lane, kv_len, kv_head, (t + 1) * kKvTileRows);
+    // tile t + 1 is fetched (its slots arrived during the previous iteration) and tile t + 2 is looked up
+    // while tile t is used
+    if (t + 1 < tiles_wg) issue_tile_loads(slots, a, smem + ((t + 1) & 1) * G::kStageBytes, wave, lane, kv_head);
+    if (t + 2 < tiles_wg) fetch_tile_slots(next_slots, a, table, wave, lane, kv_len, (t + 2) * kKvTileRows);
     if (t < tiles_wave) {
       const int kv0 = t * kKvTileRows;
       w.template tile<2>(stage, kv0, kv0 + kKvTileRows - 1 > min_lim);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    slots = next_slots;
   }
   w.store_row(0, active && q0 + m < q_len ? a.out + ((q_start + q0 + m) * a.n_q_heads + head) * D : nullptr);
 #else
