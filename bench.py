@@ -62,14 +62,19 @@ class DeviceBatch:
         # attention kernel's persistent workgroups leave as they run out of work.
         self.side = torch.cuda.Stream(device=dev) if w.kv_cache else None
 
-    def step(self, i: int, events=None, two_streams=False):
+    def step(self, i: int, events=None, two_streams=False, workgroups_per_cu=None):
         """One pass of the whole path over one batch.  two_streams: the KV scatter goes to the side
-        stream, behind the attention launch (call drain() before reading the clock)."""
+        stream, behind the attention launch (call drain() before reading the clock).  workgroups_per_cu:
+        the attention kernel leaves room on every compute unit for another stream's kernels."""
         h, w, s = self.hydra, self.w, self.sets[i % len(self.sets)]
         h.hydra_attn_build_worklist(self.cu, w.total_tokens, w.max_seqlen, w.n_q_heads, w.n_kv_heads, w.head_dim, w.causal, self.ws)
         if events is not None:
             events[0].record()
-        h.hydra_attn_varlen_fwd_prebuilt(s["q"], s["k"], s["v"], self.cu, w.max_seqlen, w.causal, w.softmax_scale, s["out"], self.ws)
+        if workgroups_per_cu is None:
+            h.hydra_attn_varlen_fwd_prebuilt(s["q"], s["k"], s["v"], self.cu, w.max_seqlen, w.causal, w.softmax_scale, s["out"], self.ws)
+        else:
+            h.hydra_attn_varlen_fwd_shared(s["q"], s["k"], s["v"], self.cu, w.max_seqlen, w.causal, w.softmax_scale, s["out"], self.ws,
+                                           workgroups_per_cu)
         if events is not None:
             events[1].record()
         if w.kv_cache:
@@ -180,8 +185,63 @@ def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode"
         run(c)  # warm-up
     seq, con = run(False), run(True)
     flops = we.attention_flops() + wp.attention_flops()
-    return {"encode": encode, "prefill": prefill, "steps": steps, "ms_sequential": seq * 1e3, "ms_two_streams": con * 1e3,
-            "tflops_sequential": flops / seq * 1e-12, "tflops_two_streams": flops / con * 1e-12, "speedup": seq / con}
+    report = {"encode": encode, "prefill": prefill, "steps": steps, "ms_sequential": seq * 1e3, "ms_two_streams": con * 1e3,
+              "tflops_sequential": flops / seq * 1e-12, "tflops_two_streams": flops / con * 1e-12, "speedup": seq / con}
+    del bp
+    report["encode_decode"] = encode_beside_decode(dev, be, se, sp, n_sets, steps)
+    return report
+
+
+def encode_beside_decode(dev, be: DeviceBatch, se, sd, n_sets: int, steps: int, n_requests: int = 256, kv_len: int = 1024):
+    """The pairing the paper's two-stream experiment uses (Section 5: encode beside decode, context length 1024):
+    encode attention (matrix-bound) on one stream, decode attention over the paged cache (memory-bound) on the
+    other, as many decode launches per encode launch as take about the same time.  Three ways: one after the
+    other; launched together with the encode kernel at its own size (its persistent workgroups hold every
+    compute unit's registers, so the decode kernel only gets what drains); launched together with the encode
+    kernel at one workgroup per compute unit (hydra_attn_varlen_fwd_shared), so that both run on every compute unit."""
+    import paper_2505_12658_amd as hydra
+
+    we = be.w
+    h = si.HybridBatch("qwen2vl_7b_decode", [1] * n_requests, [kv_len] * n_requests, 28, 4, 128, seed=3)
+    sets = []
+    for i in range(n_sets):
+        q, kc, vc, tables = si.make_paged_inputs(h)
+        sets.append((q.to(dev), kc.to(dev), vc.to(dev), torch.from_numpy(tables).to(dev), torch.empty(q.shape, dtype=torch.bfloat16, device=dev)))
+    cu = torch.from_numpy(h.cu_seqlens_q).to(dev)
+    kv_lens = torch.tensor(h.kv_lens, dtype=torch.int32, device=dev)
+
+    def decode(i):
+        q, kc, vc, tables, out = sets[i % n_sets]
+        hydra.hydra_attn_paged_fwd(q, kc, vc, tables, cu, kv_lens, 1, h.softmax_scale, out=out, use_workspace=False)
+
+    def run(mode: str, n_dec: int, per_cu=None):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            if mode != "decode":
+                with torch.cuda.stream(se):
+                    be.step(i, workgroups_per_cu=per_cu)
+            if mode == "sequential":
+                sd.wait_stream(se)
+            if mode != "encode":
+                with torch.cuda.stream(sd):
+                    for j in range(n_dec):
+                        decode(i * n_dec + j)
+            if mode == "sequential":
+                se.wait_stream(sd)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    run("encode", 1), run("decode", 1)  # warm-up
+    t_enc, t_dec = run("encode", 1), run("decode", 1)
+    n_dec = max(1, round(t_enc / t_dec))
+    for args in (("sequential", n_dec), ("together", n_dec), ("together", n_dec, 1)):
+        run(*args)
+    t_dec_n, seq, con, shared = run("decode", n_dec), run("sequential", n_dec), run("together", n_dec), run("together", n_dec, 1)
+    return {"encode": we.name, "decode": f"{n_requests} requests x {kv_len} tokens of context, Qwen2-VL-7B heads", "decode_launches_per_encode_launch": n_dec,
+            "steps": steps, "ms_encode_alone": t_enc * 1e3, "ms_decode_alone": t_dec_n * 1e3, "ms_encode_alone_one_workgroup_per_cu": run("encode", 1, 1) * 1e3,
+            "ms_sequential": seq * 1e3, "ms_two_streams": con * 1e3, "ms_two_streams_shared_cus": shared * 1e3,
+            "speedup_two_streams": seq / con, "speedup_two_streams_shared_cus": seq / shared}
 
 
 def paged_attention(dev, n_sets: int, steps: int):

@@ -108,6 +108,27 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * hydra_attn_varlen_fwd_prebuilt for an instance that runs its vision encoder and its language model
+ * on two streams at once (Section 4.3).  The attention kernel is made of persistent workgroups that
+ * by default take every compute unit's registers whole, so a kernel launched beside it on another
+ * stream only gets the compute units as they drain.  Here the caller says how many persistent
+ * workgroups per compute unit the kernel may start:
+ *
+ *   workgroups_per_cu  >= 1 (otherwise HYDRA_ERR_INVALID_ARG); values above the kernel's own number
+ *        (3 at head_dim 64, else 2) mean that number.  With 1, half (two thirds at head_dim 64) of every
+ *        compute unit's registers and most of its LDS stay free for the other stream's kernels.
+ *
+ * Results are bit-identical to hydra_attn_varlen_fwd_prebuilt for every value (work items are
+ * independent; only their placement changes).  Everything else as for hydra_attn_varlen_fwd_prebuilt.
+ */
+int hydra_attn_varlen_fwd_shared(const void* q, const void* k, const void* v, void* out,
+                                 int64_t q_token_stride, int64_t k_token_stride, int64_t v_token_stride,
+                                 const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                 int32_t causal, float softmax_scale,
+                                 void* workspace, size_t workspace_bytes, int32_t workgroups_per_cu, void* stream);
+
+/*
  * Scatter of the prefill K/V of a packed batch into a paged KV cache (Section 5.1: KV-cache block
  * size 16; the per-request page tables of Section 4.3 are flattened by the caller into one slot per
  * token, slot = block_id * block_size + offset_in_block).

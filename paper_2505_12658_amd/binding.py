@@ -40,6 +40,8 @@ def load_library() -> ctypes.CDLL:
                                               vp, sz, vp]
         lib.hydra_attn_varlen_fwd_prebuilt.restype = ctypes.c_int
         lib.hydra_attn_varlen_fwd_prebuilt.argtypes = lib.hydra_attn_varlen_fwd.argtypes
+        lib.hydra_attn_varlen_fwd_shared.restype = ctypes.c_int
+        lib.hydra_attn_varlen_fwd_shared.argtypes = lib.hydra_attn_varlen_fwd.argtypes[:-1] + [i32, vp]
         lib.hydra_attn_build_worklist.restype = ctypes.c_int
         lib.hydra_attn_build_worklist.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         lib.hydra_kv_cache_write.restype = ctypes.c_int
@@ -145,6 +147,26 @@ def hydra_attn_varlen_fwd_prebuilt(q: torch.Tensor, k: torch.Tensor, v: torch.Te
                                             workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_attn_varlen_fwd_prebuilt")
+    return out
+
+
+def hydra_attn_varlen_fwd_shared(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int,
+                                 causal: bool, softmax_scale: float, out: torch.Tensor, workspace: torch.Tensor, workgroups_per_cu: int,
+                                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """hydra_attn_varlen_fwd_prebuilt with at most `workgroups_per_cu` persistent workgroups per compute unit, for a caller
+    that runs another kernel beside it on a second stream."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _check_token_major(t, n)
+    N, Hq, d = q.shape
+    if not out.is_contiguous() or out.shape != (N, Hq, d) or out.dtype != torch.bfloat16:
+        raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    rc = lib.hydra_attn_varlen_fwd_shared(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), q.stride(0), k.stride(0),
+                                          v.stride(0), cu_seqlens.data_ptr(), cu_seqlens.numel() - 1, N, int(max_seqlen), Hq,
+                                          k.shape[1], d, int(bool(causal)), float(softmax_scale), workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), int(workgroups_per_cu), _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_varlen_fwd_shared")
     return out
 
 

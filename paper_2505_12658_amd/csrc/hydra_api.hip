@@ -30,10 +30,14 @@ unsigned compute_units() {
 // The fast kernel over the whole work list, then the careful kernel over whatever it flagged
 // (normally nothing: a few workgroups read the flags and leave).
 template <int D>
-hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned compute_units, hipStream_t stream) {
+hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned compute_units, int workgroups_per_cu, hipStream_t stream) {
   // two or three persistent workgroups per compute unit (each takes its share of registers and LDS):
-  // while one is loading Q, storing O or between key blocks, the others' matrix work fills the SIMDs
-  const unsigned grid = hydra::kWorkgroupsPerCu<D> * compute_units;
+  // while one is loading Q, storing O or between key blocks, the others' matrix work fills the SIMDs.
+  // A caller that runs another kernel beside this one asks for fewer (workgroups_per_cu > 0); any number
+  // of workgroups drains the queues.
+  const unsigned per_cu = workgroups_per_cu > 0 && workgroups_per_cu < hydra::kWorkgroupsPerCu<D> ? (unsigned)workgroups_per_cu
+                                                                                                  : (unsigned)hydra::kWorkgroupsPerCu<D>;
+  const unsigned grid = per_cu * compute_units;
   const unsigned careful_grid = compute_units;
   if (causal) {
     hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
@@ -136,10 +140,13 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
-int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride,
-                                   int64_t k_token_stride, int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch,
-                                   int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                   int32_t causal, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// The attention launch against a prebuilt work list; workgroups_per_cu == 0: the kernel's own number.
+int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
+                  int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
+                  size_t workspace_bytes, int32_t workgroups_per_cu, void* stream) {
   if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
   if (batch == 0 || total_tokens == 0) return HYDRA_OK;
@@ -182,11 +189,31 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err;
   switch (head_dim) {
-    case 64: err = launch_attn<64>(causal != 0, args, grid, s); break;
-    case 80: err = launch_attn<80>(causal != 0, args, grid, s); break;
-    default: err = launch_attn<128>(causal != 0, args, grid, s); break;
+    case 64: err = launch_attn<64>(causal != 0, args, grid, workgroups_per_cu, s); break;
+    case 80: err = launch_attn<80>(causal != 0, args, grid, workgroups_per_cu, s); break;
+    default: err = launch_attn<128>(causal != 0, args, grid, workgroups_per_cu, s); break;
   }
   return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride,
+                                   int64_t k_token_stride, int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch,
+                                   int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                   int32_t causal, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_prebuilt(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                       n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, workspace, workspace_bytes, 0, stream);
+}
+
+int hydra_attn_varlen_fwd_shared(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride,
+                                 int64_t k_token_stride, int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch,
+                                 int32_t total_tokens, int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                 int32_t causal, float softmax_scale, void* workspace, size_t workspace_bytes,
+                                 int32_t workgroups_per_cu, void* stream) {
+  if (workgroups_per_cu < 1) return HYDRA_ERR_INVALID_ARG;
+  return attn_prebuilt(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                       n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, workspace, workspace_bytes, workgroups_per_cu, stream);
 }
 
 int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,

@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_paged_workspace_bytes", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_workspace_bytes",
+    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_paged_workspace_bytes", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_varlen_fwd_shared", "hydra_attn_workspace_bytes",
                      "hydra_kv_cache_write", "hydra_page_cache_gather", "hydra_page_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -81,6 +81,17 @@ def test_attn_argument_errors(lib):
     # empty batches succeed without touching any pointer
     assert _attn(lib, batch=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0
     assert _attn(lib, total=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0
+
+
+def test_shared_attn_argument_errors(lib):
+    """The variant for two-stream callers checks its own argument before anything else and otherwise
+    validates like the plain call (fake addresses: every case is rejected on the host)."""
+    def call(per_cu, q=16, d=64, ws_bytes=1 << 20):
+        return lib.hydra_attn_varlen_fwd_shared(q, 16, 16, 16, 128, 128, 128, 16, 1, 8, 8, 2, 2, d, 0, 0.125, 16, ws_bytes, per_cu, None)
+    assert call(0) == 1 and call(-3) == 1
+    assert call(1, q=None) == 1
+    assert call(1, d=96) == 2
+    assert call(2, ws_bytes=8) == 3
 
 
 def _kvw(lib, k=16, v=16, ks=128, vs=128, kc=16, vc=16, slots=16, total=4, hkv=2, d=64, bs=16, nb=4, stream=None):

@@ -166,6 +166,45 @@ def test_large_scores_take_careful_path(d, causal):
     assert torch.equal(again.view(torch.int16), out.view(torch.int16))
 
 
+@pytest.mark.parametrize("d,hq,hkv,causal", [(64, 4, 2, False), (80, 2, 2, False), (128, 7, 1, True)])
+def test_shared_variant_matches_plain_call(d, hq, hkv, causal):
+    """The variant for two-stream callers (fewer persistent workgroups per compute unit) against the
+    oracle, and bit for bit against the plain call, for one workgroup per CU, the kernel's own number and
+    a larger request; once more with a paged decode step running on a second stream at the same time."""
+    hydra = _hydra()
+    w = si.custom([300, 17, 1, 640, 129, 64, 1000], hq, hkv, d, causal, seed=5)
+    q, k, v = si.make_qkv(w)
+    dev = torch.device("cuda:0")
+    cu = torch.from_numpy(w.cu_seqlens).to(dev)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    ws = hydra.hydra_attn_build_worklist(cu, w.total_tokens, w.max_seqlen, hq, hkv, d, causal)
+    plain = torch.empty_like(qd)
+    hydra.hydra_attn_varlen_fwd_prebuilt(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, plain, ws)
+    torch.cuda.synchronize()
+    _check(plain, c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, causal, w.softmax_scale))
+    for per_cu in (1, 2, 3, 100):
+        out = torch.full_like(qd, float("nan"))
+        hydra.hydra_attn_varlen_fwd_shared(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, out, ws, per_cu)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), plain.view(torch.int16)), per_cu
+    # beside a decode step on another stream
+    h = si.HybridBatch("decode", [1] * 64, [1024] * 64, 28, 4, 128, seed=9)
+    pq, kc, vc, tables = si.make_paged_inputs(h)
+    pq, kc, vc, tables = pq.to(dev), kc.to(dev), vc.to(dev), torch.from_numpy(tables).to(dev)
+    cu_q, kv_lens = torch.from_numpy(h.cu_seqlens_q).to(dev), torch.tensor(h.kv_lens, dtype=torch.int32, device=dev)
+    alone = hydra.hydra_attn_paged_fwd(pq, kc, vc, tables, cu_q, kv_lens, 1, h.softmax_scale, use_workspace=False)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(device=dev)
+    out = torch.full_like(qd, float("nan"))
+    beside = torch.empty_like(alone)
+    hydra.hydra_attn_varlen_fwd_shared(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, out, ws, 1)
+    with torch.cuda.stream(side):
+        hydra.hydra_attn_paged_fwd(pq, kc, vc, tables, cu_q, kv_lens, 1, h.softmax_scale, out=beside, use_workspace=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), plain.view(torch.int16))
+    assert torch.equal(beside.view(torch.int16), alone.view(torch.int16))
+
+
 def test_many_short_sequences():
     """More sequences than the work-list builder keeps in LDS (4096): exercises its global-memory path,
     queue rows beyond one wave, and zero-length sequences in between."""
