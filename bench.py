@@ -86,8 +86,26 @@ class DeviceBatch:
                 events[2].record()
 
 
+SETTLE_SECONDS = 0.15
+
+
+def settle(launch, seconds: float = SETTLE_SECONDS):
+    """Keeps the device under the load about to be measured until its clocks have settled: after any idle
+    stretch (input generation on the host, uploads) the first ~50 ms of kernels run up to 20 % slower than
+    the steady state.  Untimed; the stated warm-up steps and the timed steps follow without a gap."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            launch(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def time_steps(batch: DeviceBatch, steps: int, warmup: int, two_streams: bool = False):
     """Wall-clock over exactly `steps` steps, bracketed by device synchronisation (all streams)."""
+    settle(lambda i: batch.step(i, two_streams=two_streams))
     for i in range(warmup):
         batch.step(i, two_streams=two_streams)
     torch.cuda.synchronize()
@@ -102,7 +120,7 @@ def time_kernels(batch: DeviceBatch, steps: int):
     """Same steps again with HIP events (on the launch stream) around the attention kernel and the
     KV scatter.  Returns average attention-kernel and KV-write durations in seconds."""
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-    torch.cuda.synchronize()
+    settle(batch.step)
     for i in range(steps):
         batch.step(i, evs[i])
     torch.cuda.synchronize()
@@ -271,10 +289,8 @@ def paged_attention(dev, n_sets: int, steps: int):
             q, kc, vc, tables, out = sets[i % n_sets]
             hydra.hydra_attn_paged_fwd(q, kc, vc, tables, cu, kv_lens, h.max_q_len, h.softmax_scale, out=out, workspace=ws)
 
-        for i in range(5):
-            launch(i)
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        torch.cuda.synchronize()
+        settle(launch)
         for i, (e0, e1) in enumerate(evs):
             e0.record()
             launch(i)
@@ -309,10 +325,8 @@ def image_cache(dev, steps: int):
                  "peak": PEAK_HBM_GBS, "unit": "GB/s"}
         for name, fn in (("write", lambda: hydra.hydra_page_cache_write(rows, cache, slots)),
                          ("gather", lambda: hydra.hydra_page_cache_gather(cache, slots, out))):
-            for _ in range(5):
-                fn()
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-            torch.cuda.synchronize()
+            settle(lambda i: fn())
             for e0, e1 in evs:
                 e0.record()
                 fn()
