@@ -14,7 +14,9 @@
 // workgroups of that die pick the run up together and the rows come from memory once per die
 // instead of once per item.  Pairs are ranked by sequence length, longest first, and dealt to the
 // queues in serpentine order (0..7, 7..0, ...), which keeps the queues' total work level and puts
-// the small items at the end of every queue, where they even out the finish.
+// the short sequences at the end of every queue; the last kTailSort items of a queue are then
+// re-ordered by descending cost, so that the items claimed last are the cheapest and the
+// workgroups finish close together.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,6 +28,16 @@ namespace hydra {
 constexpr int kPrepassThreads = 1024;
 constexpr int kPrepassLdsSeqs = 4096;    // sequence lengths kept in LDS for the ranking
 constexpr int kPrepassLdsPrefix = 8192;  // queue prefix entries kept in LDS
+constexpr int kTailSort = 256;          // at most this many items at the end of every queue are ordered by cost
+
+// Items at the end of a queue that step 4 of the prepass sorts.  An item covers 128 query rows of one head, so
+// the pairs that a tail of T items touches hold about T * 128 / group tokens of K and V: the tail is as long as
+// 3 MB of such rows allow (a die's L2 has 4 MB), at most kTailSort.
+inline int tail_sort_items(int group, int head_dim) {
+  const int64_t bytes_per_item = (int64_t)kWavesPerItem * kWaveTileRows * head_dim * 4 / group;
+  const int64_t fit = ((int64_t)3 << 20) / (bytes_per_item > 0 ? bytes_per_item : 1);
+  return (int)(fit < kTailSort ? fit : kTailSort);
+}
 
 // Workspace layout:
 //   WorkControl                          (counts, queue starts, one cache line per queue head)
@@ -78,7 +90,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
                                                                          WorkControl* __restrict__ ctrl, int32_t* __restrict__ sorted_seq,
                                                                          int32_t* __restrict__ queue_prefix_global, int rows,
                                                                          WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags,
-                                                                         int capacity) {
+                                                                         int capacity, int tail_items) {
   __shared__ int s_len[kPrepassLdsSeqs];
   __shared__ int s_start[kPrepassLdsSeqs];
   __shared__ int s_sorted[kPrepassLdsSeqs];
@@ -180,6 +192,61 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
       if (base + j < total) items[base + j] = make_int4(start, len, i * kWavesPerItem, kv_head);
     }
   }
+
+  // 4. the last tail_items (<= kTailSort) items of every queue are put in order of descending cost (ties keep
+  // their order).  Workgroups finish within about one item of each other, and an item is claimed one round
+  // before it runs: what matters for the end of the kernel is that the items claimed last are the cheap ones.
+  // The runs of step 3 end with the shortest sequences, but every run still goes from its dearest item to its
+  // cheapest.  (Only a tail, sized by the caller so that the K/V rows of the pairs in it fit the die's L2
+  // together: sorted, the items of one pair run apart in time, and rows that have left the L2 in between come
+  // from memory once per item instead of once per die.)
+  __threadfence_block();
+  __syncthreads();
+  int* s_cost = s_prefix;  // step 3 was the last reader of the queue prefixes
+  static_assert(kXcds * kTailSort <= kPrepassLdsPrefix && (kXcds * kTailSort) % kPrepassThreads == 0, "tail entries per thread");
+  constexpr int kPerThread = kXcds * kTailSort / kPrepassThreads;
+  WorkItem held[kPerThread];
+  int place[kPerThread];
+#pragma unroll
+  for (int k = 0; k < kPerThread; ++k) {
+    const int e = tid + k * kPrepassThreads;
+    const int x = e / kTailSort, o = e % kTailSort;
+    const int q_begin = s_queue_start[x], q_end = s_queue_start[x + 1];
+    const int tail = q_end - tail_items > q_begin ? q_end - tail_items : q_begin;
+    place[k] = -1;
+    int cost = -1;
+    if (o < tail_items && tail + o < q_end) {
+      held[k] = items[tail + o];
+      place[k] = tail;
+      const int len = held[k].y;
+      cost = (len + kKvTileRows - 1) / kKvTileRows;
+      if (CAUSAL) {
+        const int wave_tiles = ((len + kWaveTileRows - 1) / kWaveTileRows) * group;
+        const int f_last = held[k].z + kWavesPerItem - 1 < wave_tiles ? held[k].z + kWavesPerItem - 1 : wave_tiles - 1;
+        const int keys = (f_last / group + 1) * kWaveTileRows;  // keys visible to the item's last query tile
+        if (keys < len) cost = (keys + kKvTileRows - 1) / kKvTileRows;
+      }
+    }
+    s_cost[e] = cost;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kPerThread; ++k) {
+    if (place[k] < 0) continue;
+    const int e = tid + k * kPrepassThreads;
+    const int x = e / kTailSort, o = e % kTailSort;
+    const int mine = s_cost[e];
+    int rank = 0;
+    for (int other = 0; other < kTailSort; ++other) {
+      const int c = s_cost[x * kTailSort + other];  // (-1 past the end of a short queue: never ahead of a real item)
+      rank += (c > mine || (c == mine && other < o)) ? 1 : 0;
+    }
+    place[k] += rank;
+  }
+  __syncthreads();  // every thread holds its items: the tail can be overwritten
+#pragma unroll
+  for (int k = 0; k < kPerThread; ++k)
+    if (place[k] >= 0) items[place[k]] = held[k];
 }
 
 }  // namespace hydra

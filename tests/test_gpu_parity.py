@@ -205,6 +205,49 @@ def test_shared_variant_matches_plain_call(d, hq, hkv, causal):
     assert torch.equal(beside.view(torch.int16), alone.view(torch.int16))
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 64)])
+def test_worklist_covers_every_tile_once_and_ends_with_cheap_items(hq, hkv, d, causal):
+    """The device-built work list read back from the workspace: every group of four wave tiles of every
+    (sequence, KV head) appears exactly once, the eight queues partition the list, and the end of every
+    queue (as many items as the library says it orders) is in order of non-increasing cost."""
+    hydra = _hydra()
+    rng = np.random.default_rng(3)
+    lengths = rng.integers(1, 900, size=37).tolist() + [0, 2048, 33]
+    w = si.custom(lengths, hq, hkv, d, causal, seed=1)
+    dev = torch.device("cuda:0")
+    cu = torch.from_numpy(w.cu_seqlens).to(dev)
+    ws = hydra.hydra_attn_build_worklist(cu, w.total_tokens, w.max_seqlen, hq, hkv, d, causal)
+    torch.cuda.synchronize()
+    words = ws.cpu().numpy().view(np.int32)
+    g = hq // hkv
+    expected = set()
+    for b, L in enumerate(lengths):
+        wave_tiles = -(-L // 32) * g
+        for kv in range(hkv):
+            for f0 in range(0, wave_tiles, 4):
+                expected.add((int(w.cu_seqlens[b]), L, f0, kv))
+    n_items, starts = int(words[0]), words[1:10]
+    assert n_items == len(expected) and starts[0] == 0 and starts[8] == n_items and (np.diff(starts) >= 0).all()
+    rows = (w.batch * hkv + 7) // 8
+    items_at = (1152 + 4 * w.batch + 32 * rows + 15) // 16 * 16
+    items = words[items_at // 4: items_at // 4 + 4 * n_items].reshape(n_items, 4)
+    assert set(map(tuple, items.tolist())) == expected
+
+    def cost(start, L, f0, kv):
+        tiles = -(-L // 64)
+        if causal:
+            f_last = min(f0 + 3, -(-L // 32) * g - 1)
+            tiles = min(tiles, -(-((f_last // g + 1) * 32) // 64))
+        return tiles
+
+    tail = min(256, (3 << 20) // (4 * 32 * d * 4 // g))
+    for x in range(8):
+        q = [cost(*it) for it in items[starts[x]:starts[x + 1]].tolist()]
+        t = q[-tail:]
+        assert all(a >= b for a, b in zip(t, t[1:])), (x, t)
+
+
 def test_many_short_sequences():
     """More sequences than the work-list builder keeps in LDS (4096): exercises its global-memory path,
     queue rows beyond one wave, and zero-length sequences in between."""
