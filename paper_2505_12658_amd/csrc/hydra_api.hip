@@ -133,10 +133,10 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
   const int group = n_q_heads / n_kv_heads;
   const int tail_items = hydra::tail_sort_items(group, head_dim);
   if (causal)
-    hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
+    hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(hydra::prepass_workgroups(lay.capacity)), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
                        group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
   else
-    hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(1), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
+    hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(hydra::prepass_workgroups(lay.capacity)), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
                        group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
   return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }

@@ -28,7 +28,7 @@ namespace hydra {
 constexpr int kPrepassThreads = 1024;
 constexpr int kPrepassLdsSeqs = 4096;    // sequence lengths kept in LDS for the ranking
 constexpr int kPrepassLdsPrefix = 8192;  // queue prefix entries kept in LDS
-constexpr int kTailSort = 256;          // at most this many items at the end of every queue are ordered by cost
+constexpr int kTailSort = 128;          // at most this many items at the end of every queue are ordered by cost
 
 // Items at the end of a queue that step 4 of the prepass sorts.  An item covers 128 query rows of one head, so
 // the pairs that a tail of T items touches hold about T * 128 / group tokens of K and V: the tail is as long as
@@ -82,6 +82,12 @@ __device__ __forceinline__ int items_of_sequence(int len, int group) {
   return (tok_tiles * group + kWavesPerItem - 1) / kWavesPerItem;
 }
 
+// Workgroups of the prepass: one per 1024 places of the list, at least one per queue (its tail), at most 64.
+inline unsigned prepass_workgroups(size_t capacity) {
+  const size_t g = (capacity + kPrepassThreads - 1) / kPrepassThreads;
+  return (unsigned)(g < (size_t)kXcds ? (size_t)kXcds : g > 64 ? 64 : g);
+}
+
 // queue of the pair with rank r (row r / 8): serpentine dealing
 __device__ __forceinline__ int pair_rank(int row, int queue) { return row * kXcds + ((row & 1) ? kXcds - 1 - queue : queue); }
 
@@ -95,12 +101,19 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   __shared__ int s_start[kPrepassLdsSeqs];
   __shared__ int s_sorted[kPrepassLdsSeqs];
   __shared__ int s_prefix[kPrepassLdsPrefix];
+  __shared__ __attribute__((aligned(16))) int s_key[kPrepassThreads / 2];  // step 1: rank counters; step 4: sort keys (kTailSort of them)
+  __shared__ __attribute__((aligned(16))) WorkItem s_tail[kTailSort];
   __shared__ int s_queue_len[kXcds];
   __shared__ int s_queue_start[kXcds + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < capacity; i += kPrepassThreads) redo_flags[i] = 0;
-  if (tid < kXcds) ctrl->queue_head[tid * kHeadStride] = 0;
-  if (tid == 0) {
+  // Every workgroup of the grid derives the ranking and the queue layout for itself (steps 1 and 2: a few
+  // microseconds, and no synchronisation between workgroups is needed); the places of the list are then shared
+  // out over the grid (step 3), and workgroup x < 8 also orders the tail of queue x (step 4).  Workgroup 0
+  // writes the control block.
+  const bool leader = blockIdx.x == 0;
+  for (int i = blockIdx.x * kPrepassThreads + tid; i < capacity; i += gridDim.x * kPrepassThreads) redo_flags[i] = 0;
+  if (leader && tid < kXcds) ctrl->queue_head[tid * kHeadStride] = 0;
+  if (leader && tid == 0) {
     ctrl->redo_any = 0;
     ctrl->careful_done = 0;
   }
@@ -118,17 +131,38 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   auto length_of = [&](int b) { return b < kPrepassLdsSeqs ? s_len[b] : cu[b + 1] - cu[b]; };
   auto start_of = [&](int b) { return b < kPrepassLdsSeqs ? s_start[b] : cu[b]; };
 
-  // 1. rank the sequences by descending length (ties by index): each thread counts who precedes its sequence
-  for (int b = tid; b < batch; b += kPrepassThreads) {
-    const int mine = length_of(b);
-    int rank = 0;
-    for (int o = 0; o < batch; ++o) {
-      const int other = length_of(o);
-      rank += (other > mine || (other == mine && o < b)) ? 1 : 0;
+  // 1. rank the sequences by descending length (ties by index): count who precedes each sequence.  Batches of
+  // up to half the workgroup have several threads per sequence, each counting a share of the others.
+  if (batch <= kPrepassThreads / 2) {
+    int* s_rank = s_key;  // (unused until step 3)
+    const int parts = kPrepassThreads / batch;
+    if (tid < batch) s_rank[tid] = 0;
+    __syncthreads();
+    const int b = tid / parts, part = tid - b * parts;
+    if (b < batch) {
+      const int mine = s_len[b];
+      int count = 0;
+      for (int o = part; o < batch; o += parts) {
+        const int other = s_len[o];
+        count += (other > mine || (other == mine && o < b)) ? 1 : 0;
+      }
+      if (count) atomicAdd(&s_rank[b], count);
     }
-    sorted[rank] = b;
+    __syncthreads();
+    if (tid < batch) s_sorted[s_rank[tid]] = tid;
+  } else {
+    for (int b = tid; b < batch; b += kPrepassThreads) {
+      const int mine = length_of(b);
+      int rank = 0;
+#pragma unroll 8
+      for (int o = 0; o < batch; ++o) {
+        const int other = length_of(o);
+        rank += (other > mine || (other == mine && o < b)) ? 1 : 0;
+      }
+      sorted[rank] = b;
+    }
   }
-  __threadfence_block();
+  if (!in_lds) __threadfence_block();  // (a fence also waits for every store this thread has in flight)
   __syncthreads();
 
   // 2. per queue, the running item count over its pairs (one pair per row): wave x scans queue x
@@ -152,7 +186,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
     }
     if (lane == 0) s_queue_len[wave] = carry;
   }
-  __threadfence_block();
+  if (queue_prefix != s_prefix) __threadfence_block();
   __syncthreads();
   {
     // every thread computes the queue starts for itself; threads 0 .. 8 publish them
@@ -167,86 +201,119 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
     if (tid <= kXcds) {
       if (mine > run) mine = run;
       s_queue_start[tid] = mine;
-      ctrl->xcd_start[tid] = mine;
+      if (leader) ctrl->xcd_start[tid] = mine;
     }
-    if (tid == 0) ctrl->n_items = run;
+    if (leader && tid == 0) ctrl->n_items = run;
   }
   __syncthreads();
 
-  // 3. four threads per pair write the pair's items (thread k takes items k, k + 4, ...): the pair's place in
-  // its queue is known from step 2, so an item costs a few instructions
+  // 3. one thread per place of the list (consecutive threads write consecutive items).  The queue of a place
+  // follows from the queue starts, its pair from a binary search over the queue's prefix (step 2), and the
+  // item from the distance to the pair's first place.
   const int total = s_queue_start[kXcds];
-  constexpr int kThreadsPerPair = 4;
-  for (int slot = tid / kThreadsPerPair; slot < rows * kXcds; slot += kPrepassThreads / kThreadsPerPair) {
-    const int x = slot / rows, row = slot - x * rows;
-    const int r = pair_rank(row, x);
-    if (r >= n_pairs) continue;
-    const int b = sorted[r / n_kv_heads];
-    const int kv_head = r % n_kv_heads;
+  // item of place p, which lies in queue x; cost = 64-key tiles the item streams (those visible to its last query tile)
+  auto item_at = [&](int p, int x, int& cost) -> WorkItem {
+    const int local = p - s_queue_start[x];
+    // the last row that starts at or before this place (a row without items starts where the next one does;
+    // rows past the last pair start at the end of the queue)
+    const int* prefix = queue_prefix + x * rows;
+    int lo = 0, hi = rows - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (prefix[mid] <= local) lo = mid; else hi = mid - 1;
+    }
+    int r = pair_rank(lo, x);
+    if (r >= n_pairs) r = n_pairs - 1;  // cannot happen for valid cu_seqlens
+    const int seq_rank = r / n_kv_heads;
+    const int b = sorted[seq_rank];
+    const int kv_head = r - seq_rank * n_kv_heads;
     const int start = start_of(b), len = length_of(b);
     const int n = items_of_sequence(len, group);
-    const int base = s_queue_start[x] + queue_prefix[slot];
-    for (int j = tid % kThreadsPerPair; j < n; j += kThreadsPerPair) {
-      // most expensive first: under the causal mask the cost grows with the item's position in the sequence
-      const int i = CAUSAL ? n - 1 - j : j;
-      if (base + j < total) items[base + j] = make_int4(start, len, i * kWavesPerItem, kv_head);
+    int j = local - prefix[lo];
+    if (j >= n) j = n - 1;  // (same remark)
+    // most expensive first: under the causal mask the cost grows with the item's position in the sequence
+    const int i = CAUSAL ? n - 1 - j : j;
+    cost = (len + kKvTileRows - 1) / kKvTileRows;
+    if (CAUSAL) {
+      const int wave_tiles = ((len + kWaveTileRows - 1) / kWaveTileRows) * group;
+      const int f_last = i * kWavesPerItem + kWavesPerItem - 1 < wave_tiles ? i * kWavesPerItem + kWavesPerItem - 1 : wave_tiles - 1;
+      const int keys = (f_last / group + 1) * kWaveTileRows;
+      if (keys < len) cost = (keys + kKvTileRows - 1) / kKvTileRows;
     }
+    return make_int4(start, len, i * kWavesPerItem, kv_head);
+  };
+  auto tail_of = [&](int x) {  // first place of queue x that step 4 orders
+    const int q_begin = s_queue_start[x], q_end = s_queue_start[x + 1];
+    return q_end - tail_items > q_begin ? q_end - tail_items : q_begin;
+  };
+  for (int p = blockIdx.x * kPrepassThreads + tid; p < total; p += gridDim.x * kPrepassThreads) {
+    int x = 0;
+#pragma unroll
+    for (int q = 1; q < kXcds; ++q) x += p >= s_queue_start[q] ? 1 : 0;
+    if (p >= tail_of(x)) continue;  // step 4
+    int cost;
+    items[p] = item_at(p, x, cost);
   }
 
-  // 4. the last tail_items (<= kTailSort) items of every queue are put in order of descending cost (ties keep
-  // their order).  Workgroups finish within about one item of each other, and an item is claimed one round
-  // before it runs: what matters for the end of the kernel is that the items claimed last are the cheap ones.
-  // The runs of step 3 end with the shortest sequences, but every run still goes from its dearest item to its
-  // cheapest.  (Only a tail, sized by the caller so that the K/V rows of the pairs in it fit the die's L2
-  // together: sorted, the items of one pair run apart in time, and rows that have left the L2 in between come
-  // from memory once per item instead of once per die.)
-  __threadfence_block();
+  // 4. the last tail_items (<= kTailSort) places of every queue in order of descending cost.  Workgroups finish
+  // within about one item of each other, and an item is claimed one round before it runs: what matters for the
+  // end of the kernel is that the items claimed last are the cheap ones.  The runs of step 3 end with the
+  // shortest sequences, but every run still goes from its dearest item to its cheapest.  (Only a tail, sized by
+  // the caller so that the K/V rows of the pairs in it fit the die's L2 together: sorted, the items of one pair
+  // run apart in time, and rows that have left the L2 in between come from memory once per item instead of
+  // once per die.)  Workgroup x takes queue x: its items go to LDS with a sort key, and wave 0 sorts the keys
+  if (blockIdx.x >= kXcds) return;
+  const int tail_x = tail_of(blockIdx.x), tail_n = s_queue_start[blockIdx.x + 1] - tail_x;
+  __syncthreads();  // (s_key held the rank counters of step 1)
+  if (tid < kTailSort) {
+    int key = -1;
+    if (tid < tail_n) {
+      int cost;
+      s_tail[tid] = item_at(tail_x + tid, blockIdx.x, cost);
+      key = cost * kTailSort + (kTailSort - 1 - tid);  // distinct keys; equal costs keep their order
+    }
+    s_key[tid] = key;
+  }
   __syncthreads();
-  int* s_cost = s_prefix;  // step 3 was the last reader of the queue prefixes
-  static_assert(kXcds * kTailSort <= kPrepassLdsPrefix && (kXcds * kTailSort) % kPrepassThreads == 0, "tail entries per thread");
-  constexpr int kPerThread = kXcds * kTailSort / kPrepassThreads;
-  WorkItem held[kPerThread];
-  int place[kPerThread];
+  // (distinct by construction, -1 = no item) with a bitonic network held in registers: lane l has the keys of
+  // places l, l + 64, ...
+  constexpr int kKeysPerLane = kTailSort / 64;
+  static_assert(kTailSort % 64 == 0 && (kTailSort & (kTailSort - 1)) == 0, "a power of two, whole registers");
+  if (wave == 0) {
+    int key[kKeysPerLane];
 #pragma unroll
-  for (int k = 0; k < kPerThread; ++k) {
-    const int e = tid + k * kPrepassThreads;
-    const int x = e / kTailSort, o = e % kTailSort;
-    const int q_begin = s_queue_start[x], q_end = s_queue_start[x + 1];
-    const int tail = q_end - tail_items > q_begin ? q_end - tail_items : q_begin;
-    place[k] = -1;
-    int cost = -1;
-    if (o < tail_items && tail + o < q_end) {
-      held[k] = items[tail + o];
-      place[k] = tail;
-      const int len = held[k].y;
-      cost = (len + kKvTileRows - 1) / kKvTileRows;
-      if (CAUSAL) {
-        const int wave_tiles = ((len + kWaveTileRows - 1) / kWaveTileRows) * group;
-        const int f_last = held[k].z + kWavesPerItem - 1 < wave_tiles ? held[k].z + kWavesPerItem - 1 : wave_tiles - 1;
-        const int keys = (f_last / group + 1) * kWaveTileRows;  // keys visible to the item's last query tile
-        if (keys < len) cost = (keys + kKvTileRows - 1) / kKvTileRows;
+    for (int r = 0; r < kKeysPerLane; ++r) key[r] = s_key[r * 64 + lane];
+#pragma unroll
+    for (int size = 2; size <= kTailSort; size <<= 1) {
+#pragma unroll
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        if (stride >= 64) {
+          const int rs = stride / 64;  // the partner sits in another register of the same lane
+#pragma unroll
+          for (int r = 0; r < kKeysPerLane; ++r) {
+            if (r & rs) continue;
+            const bool descending = ((r * 64) & size) == 0;
+            const int a = key[r], b = key[r | rs];
+            const bool swap = descending ? a < b : a > b;
+            key[r] = swap ? b : a;
+            key[r | rs] = swap ? a : b;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < kKeysPerLane; ++r) {
+            const int other = __shfl_xor(key[r], stride);
+            const bool descending = (((r * 64 + lane) & size) == 0);
+            const bool first = (lane & stride) == 0;  // the earlier place of the pair
+            const int hi = key[r] > other ? key[r] : other, lo = key[r] > other ? other : key[r];
+            key[r] = (first == descending) ? hi : lo;
+          }
+        }
       }
     }
-    s_cost[e] = cost;
-  }
-  __syncthreads();
 #pragma unroll
-  for (int k = 0; k < kPerThread; ++k) {
-    if (place[k] < 0) continue;
-    const int e = tid + k * kPrepassThreads;
-    const int x = e / kTailSort, o = e % kTailSort;
-    const int mine = s_cost[e];
-    int rank = 0;
-    for (int other = 0; other < kTailSort; ++other) {
-      const int c = s_cost[x * kTailSort + other];  // (-1 past the end of a short queue: never ahead of a real item)
-      rank += (c > mine || (c == mine && other < o)) ? 1 : 0;
-    }
-    place[k] += rank;
+    for (int r = 0; r < kKeysPerLane; ++r)
+      if (key[r] >= 0) items[tail_x + r * 64 + lane] = s_tail[kTailSort - 1 - (key[r] & (kTailSort - 1))];
   }
-  __syncthreads();  // every thread holds its items: the tail can be overwritten
-#pragma unroll
-  for (int k = 0; k < kPerThread; ++k)
-    if (place[k] >= 0) items[place[k]] = held[k];
 }
 
 }  // namespace hydra

@@ -241,7 +241,7 @@ def test_worklist_covers_every_tile_once_and_ends_with_cheap_items(hq, hkv, d, c
             tiles = min(tiles, -(-((f_last // g + 1) * 32) // 64))
         return tiles
 
-    tail = min(256, (3 << 20) // (4 * 32 * d * 4 // g))
+    tail = min(128, (3 << 20) // (4 * 32 * d * 4 // g))
     for x in range(8):
         q = [cost(*it) for it in items[starts[x]:starts[x + 1]].tolist()]
         t = q[-tail:]
