@@ -408,7 +408,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       const int row = flat / G::kChunks, phys = flat % G::kChunks;
       const uint32_t off = (uint32_t)row * q_row_bytes + k_swizzle<D>(row, phys) * 16;
       const uint32_t m0 = __builtin_amdgcn_readfirstlane(q_stage + i * 1024);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(off), "s"(rsrc));
+      // (nt: Q is read once; marking its lines for early replacement leaves the L2 to the K/V rows that are re-read)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen nt lds" : : "s"(m0), "v"(off), "s"(rsrc));
     }
   };
   bool q_ahead = false;      // the current item's Q loads were issued at the end of the previous round
@@ -925,7 +926,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       const uint32_t off = (uint32_t)r * out_row_bytes + chunk * 16;
       // (a store of more than 8 bytes reads its data registers a little after it issues; the wait
       // states keep the next instruction from overwriting them: the compiler does not see this store)
-      asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 1" : : "v"(piece), "v"(off), "s"(rsrc) : "memory");
+      // (nt: the output is not read again by this kernel)
+      asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen nt\n\ts_nop 1" : : "v"(piece), "v"(off), "s"(rsrc) : "memory");
     }
   }
   }  // next work item

@@ -123,7 +123,9 @@ __device__ __forceinline__ void fetch_tile_slots(TileSlots<D, KEYS, STEP>& ts, c
   }
 }
 
-template <int D, int KEYS, int STEP>
+// CPOL: cache-policy bits of the load instructions (2 = nt: lines marked for early replacement, for rows that no
+// other workgroup reads again).
+template <int CPOL = 0, int D, int KEYS, int STEP>
 __device__ __forceinline__ void issue_tile_loads(const TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, unsigned char* stage, int first, int lane,
                                                  int kv_head) {
   using G = StageGeom<D>;
@@ -138,8 +140,8 @@ __device__ __forceinline__ void issue_tile_loads(const TileSlots<D, KEYS, STEP>&
       const int phys = flat % G::kChunks;
       const uint16_t* kp = a.k_cache + ts.slot[u] * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
       const uint16_t* vp = a.v_cache + ts.slot[u] * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + kTileBytes + instr * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(kp), HYDRA_LDS_PTR(stage + instr * 1024), 16, 0, CPOL);
+      __builtin_amdgcn_global_load_lds(HYDRA_GLOBAL_PTR(vp), HYDRA_LDS_PTR(stage + kTileBytes + instr * 1024), 16, 0, CPOL);
     }
   }
 }
@@ -345,7 +347,7 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   if (h_begin + wave < h_end) fetch_tile_slots(slots, a, table, 0, lane, kv_len, (h_begin + wave) * kHalfKeys);
   for (int h = h_begin + wave; h < h_end; h += kWavesPerGroup) {
     const int kv0 = h * kHalfKeys;
-    issue_tile_loads(slots, a, stage, 0, lane, kv_head);
+    issue_tile_loads<2>(slots, a, stage, 0, lane, kv_head);  // (each key of the context is read by exactly one wave of one workgroup)
     // the next half tile's block-table lookup travels together with this one's rows
     if (h + kWavesPerGroup < h_end) fetch_tile_slots(next_slots, a, table, 0, lane, kv_len, (h + kWavesPerGroup) * kHalfKeys);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

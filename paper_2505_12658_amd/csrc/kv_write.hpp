@@ -20,6 +20,7 @@ struct KvWriteArgs {
 };
 
 constexpr int kKvWriteThreads = 256;
+typedef unsigned int piece_t __attribute__((ext_vector_type(4)));  // 16 bytes
 
 // One thread per 16-byte piece of a token row; K and V handled by the same thread.
 __global__ __launch_bounds__(kKvWriteThreads) void kv_cache_write_kernel(const KvWriteArgs a) {
@@ -30,10 +31,11 @@ __global__ __launch_bounds__(kKvWriteThreads) void kv_cache_write_kernel(const K
     const int32_t piece = (int32_t)(i - (int64_t)t * a.row16);
     const int64_t slot = a.slot_mapping[t];
     if (slot < 0) continue;
-    const uint4 kk = a.k[t * a.k_stride16 + piece];
-    const uint4 vv = a.v[t * a.v_stride16 + piece];
-    a.k_cache[slot * a.row16 + piece] = kk;
-    a.v_cache[slot * a.row16 + piece] = vv;
+    // (non-temporal on both sides: nothing here is touched twice; measured +10 % on rows of 8 KB, neutral on 1 KB)
+    const piece_t kk = __builtin_nontemporal_load(reinterpret_cast<const piece_t*>(a.k + t * a.k_stride16 + piece));
+    const piece_t vv = __builtin_nontemporal_load(reinterpret_cast<const piece_t*>(a.v + t * a.v_stride16 + piece));
+    __builtin_nontemporal_store(kk, reinterpret_cast<piece_t*>(a.k_cache + slot * a.row16 + piece));
+    __builtin_nontemporal_store(vv, reinterpret_cast<piece_t*>(a.v_cache + slot * a.row16 + piece));
   }
 }
 
