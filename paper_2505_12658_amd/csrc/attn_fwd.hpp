@@ -109,7 +109,14 @@ struct TileGeom {
   // (a tile's slot is free again after the barrier that ends the iteration consuming it)
   static constexpr int kRing = 2;
   static constexpr int kPrefetch = kRing - 1;
-  static constexpr int kLdsBytes = 2 * kRing * kTileBytes + 64;  // + slack: D=80 reads V columns 80..95
+  // D = 80: the third 32-column block of P V has 16 columns to spare.  The lanes that feed them read bf16 ones
+  // from a constant area instead of the V tile, so the matrix unit delivers the softmax row sums in output
+  // columns 80..95 and the vector unit does not have to add them up (16 additions per key block and wave).
+  // The area covers every offset a V fragment read adds to its lane address.
+  static constexpr bool kSumsFromMatrixUnit = D == 80;
+  static constexpr int kOnesBytes = kSumsFromMatrixUnit ? 9 * 1024 : 0;
+  static constexpr int kOnesAt = 2 * kRing * kTileBytes + 64;    // (+ slack behind the last V tile)
+  static constexpr int kLdsBytes = kOnesAt + kOnesBytes;
 };
 
 // XOR swizzles of the 16-byte chunk index inside an LDS row.  Chosen so that the 16 lanes the
@@ -360,6 +367,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // die this workgroup runs on (hardware id register XCC_ID, bits 3:0)
   const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
   __shared__ __attribute__((aligned(16))) int s_claim[8];
+  if constexpr (G::kSumsFromMatrixUnit) {
+    static_assert(kKvTileRows * ROWB - 8 * ROWB + 8 <= G::kOnesBytes, "a V fragment read stays inside the ones");
+    for (int i = threadIdx.x * 16; i < G::kOnesBytes; i += 256 * 16)
+      *reinterpret_cast<u32x4_t*>(HYDRA_LDS_BYTE(k_ring + G::kOnesAt + i)) = u32x4_t{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  }
 
   // Wave 0 claims the items for the whole workgroup, one round ahead: the claim for the next
   // round is issued at the top of a round, resolved (and the item read) before the hot loop, and
@@ -531,6 +543,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       // V tile "-1": the first advance brings it to tile 0
       v_addr[cc] = lds_base + (R - 1) * G::kTileBytes + R * G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
     }
+    if constexpr (G::kSumsFromMatrixUnit) {
+      // columns 80..95 (the upper 16 of the last block): ones, wherever the tile is
+      if (grp == 1) v_addr[CC - 1] = lds_base + G::kOnesAt;
+    }
   }
   auto advance_addresses = [&](int t) {  // to K tile t, V tile t - 1
     const int dk = (t % R == 0) ? -(R - 1) * G::kTileBytes : G::kTileBytes;
@@ -538,7 +554,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 #pragma unroll
     for (int s = 0; s < KS; ++s) k_addr[s] += dk;
 #pragma unroll
-    for (int cc = 0; cc < CC; ++cc) v_addr[cc] += dv;
+    for (int cc = 0; cc < CC; ++cc) v_addr[cc] += (G::kSumsFromMatrixUnit && cc == CC - 1 && grp == 1) ? 0 : dv;
   };
 
   f32x16_t o_acc[QS][CC];
@@ -598,8 +614,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[QS], bf16x8_t(&Pc)[QS][2], float(&psum)[QS]) __attribute__((always_inline)) {
     const int qs = pair / 8, r = 2 * (pair % 8);
     f32x2_t pr = {fast_exp2(Sc[qs][r]), fast_exp2(Sc[qs][r + 1])};
-    psum[qs] += pr[0];
-    psum[qs] += pr[1];
+    if constexpr (!G::kSumsFromMatrixUnit) {
+      psum[qs] += pr[0];
+      psum[qs] += pr[1];
+    }
     uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
     asm volatile("" : "+v"(packed), "+v"(psum[qs]));  // keeps this pair's work where it is written
     const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
@@ -811,6 +829,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int F_loop = odd_steps ? F : (F > 0 ? F - 1 : 0);
   int t = 1;
   StepFrags fr;
+  // Inside its pipeline steps a wave goes ahead of the SIMD's other wave when that one is between items
+  // (Q scaling, epilogue: long runs of vector instructions that would otherwise take every other issue slot).
+  __builtin_amdgcn_s_setprio(1);
   for (; t <= F_loop; ++t) {
     advance_addresses(t);
     fetch_step_frags(0, true, fr);
@@ -854,11 +875,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     wait_all_loads();
     __syncthreads();
   }
+  __builtin_amdgcn_s_setprio(0);
   // a row sum out of the safe range somewhere in this wave's rows: have the item recomputed
   if (NB > 0) {
     bool too_far = false;
 #pragma unroll
-    for (int qs = 0; qs < QS; ++qs) too_far = too_far || !(row_sum[qs] <= kMaxRowSum);
+    for (int qs = 0; qs < QS; ++qs) {
+      // (with the sums from the matrix unit: output column 80 + 4 hf of this lane's row)
+      if constexpr (G::kSumsFromMatrixUnit) row_sum[qs] = o_acc[qs][CC - 1][8];
+      too_far = too_far || !(row_sum[qs] <= kMaxRowSum);
+    }
     if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) {
       a.redo_flags[item_idx] = 1;
       a.ctrl->redo_any = 1;
@@ -894,7 +920,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     const uint32_t o_stage = k_ring + wave * (kWaveTileRows * ROWB);
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
-      const float total = sum_with_other_half(row_sum[qs]);
+      const float total = G::kSumsFromMatrixUnit ? row_sum[qs] : sum_with_other_half(row_sum[qs]);
       const float inv = 1.0f / total;
       const int r_own = 32 * qs + m;
 #pragma unroll
