@@ -57,6 +57,8 @@ struct PagedArgs {
   int32_t n_splits;
   int32_t halves_per_split;
   float* partials;  // [batch, n_kv_heads, n_splits] records of kPartialFloats<D> floats
+  int32_t batch;
+  int32_t n_tile_wgs;  // workgroups of the wave-tile form at the front of the grid (an upper bound from the host)
 };
 
 // One partial result of the packed-rows form: per row (32 rows) the maximum and the sum, then the
@@ -424,11 +426,20 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
 
 #endif  // __HIP_DEVICE_COMPILE__
 
-// grid = (1 + ceil(ceil(max_q_len / 32) * group / 4), n_kv_heads, batch).  For request z and KV head y:
-//   - q_len * group <= 32 (decode steps, chunks of a few tokens): workgroup x = gridDim.x - 1 does the whole
-//     request in the packed-rows form, the others leave at once;
-//   - otherwise workgroup x takes wave tiles 4x .. 4x + 3 in the wave-tile form, and leaves at once when the
-//     request has fewer.
+// grid = n_tile_wgs + batch * n_kv_heads * n_splits workgroups, one-dimensional.
+//   - The first n_tile_wgs workgroups run the wave-tile form: workgroup w serves KV head w % n_kv_heads and group
+//     number w / n_kv_heads in the list of all groups of four wave tiles of all requests that take this form
+//     (q_len * group > 32), which it finds for itself: the 256 threads add up the groups of a slice of the
+//     requests each, a scan over the slices gives the request, the remainder the group.  The host sizes
+//     n_tile_wgs from the total number of new tokens (it cannot see the lengths); workgroups past the last
+//     group leave at once.  Inside a request the groups are taken from the last token tile down, which see
+//     the most keys.
+//   - The others run the packed-rows form (decode steps, chunks of a few tokens): n_splits workgroups per
+//     (request, KV head), each a share of the context; requests of the other form are left at once.
+// The hardware starts workgroups in index order, so the long workgroups of a batch (prefill chunks) are all under
+// way before the short ones (decode steps) take what is left of the chip.  (A grid with one row of workgroups
+// per request made every decode request pay for the widest chunk's row: ten thousand workgroups that only
+// looked at their request's length and left, and a chunk that stood last in the batch started last.)
 // Both forms live in one kernel so that the decode requests and the prefill chunks of a batch run side by
 // side on the chip; two workgroups per compute unit (a wave keeps within 256 registers, a workgroup within
 // half of the LDS).
@@ -439,26 +450,79 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
   __shared__ float s_stats[2 * kWavesPerGroup * 64];
 
-  const int b = blockIdx.z, kv_head = blockIdx.y, f0 = blockIdx.x * kWavesPerGroup;
-  const int64_t q_start = a.cu_seqlens_q[b];
-  const int q_len = a.cu_seqlens_q[b + 1] - (int)q_start;
-  int kv_len = a.kv_lens[b];
-  {
-    // a context longer than the table can describe is cut to the table (never happens for valid input)
+  // new tokens and context of request b (context cut to what the table can describe; q_len 0: nothing to do,
+  // also for a context shorter than its new tokens, which is invalid)
+  auto lengths_of = [&](int b, int& q_len, int& kv_len) {
+    q_len = a.cu_seqlens_q[b + 1] - a.cu_seqlens_q[b];
+    kv_len = a.kv_lens[b];
     const int64_t table_keys = (int64_t)a.max_blocks_per_seq << a.block_shift;
     if (kv_len > table_keys) kv_len = (int)table_keys;
-  }
-  if (q_len <= 0 || kv_len < q_len) return;  // nothing to do (or a context shorter than its new tokens: invalid)
-  const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
-  if (q_len * a.group <= kRows) {
-    const int first_rows_wg = (int)gridDim.x - a.n_splits;
-    if ((int)blockIdx.x >= first_rows_wg)
-      run_packed_rows<D>(a, smem, s_stats, table, q_start, q_len, kv_len, kv_head, b, (int)blockIdx.x - first_rows_wg);
+    if (q_len < 0 || kv_len < q_len) q_len = 0;
+  };
+  int b, kv_head, f0 = 0;
+  if ((int)blockIdx.x >= a.n_tile_wgs) {
+    const int r = (int)blockIdx.x - a.n_tile_wgs;
+    const int pair = r / a.n_splits, split = r - pair * a.n_splits;
+    b = pair / a.n_kv_heads;
+    kv_head = pair - b * a.n_kv_heads;
+    int q_len, kv_len;
+    lengths_of(b, q_len, kv_len);
+    if (q_len == 0 || q_len * a.group > kRows) return;
+    run_packed_rows<D>(a, smem, s_stats, a.block_tables + (int64_t)b * a.max_blocks_per_seq, a.cu_seqlens_q[b], q_len, kv_len, kv_head, b, split);
     return;
   }
+  {
+    // which group of which request: see above.  Thread i adds up requests [i * per, (i + 1) * per).
+    int* s_scan = reinterpret_cast<int*>(s_stats);  // [0..3] the waves' sums, [256] = request, [257] = group
+    const int target = (int)blockIdx.x / a.n_kv_heads;
+    kv_head = (int)blockIdx.x - target * a.n_kv_heads;
+    const int per = (a.batch + 255) / 256;
+    auto groups_of = [&](int r) {
+      int q_len, kv_len;
+      lengths_of(r, q_len, kv_len);
+      if (q_len * a.group <= kRows) return 0;
+      return (((q_len + kRows - 1) / kRows) * a.group + kWavesPerGroup - 1) / kWavesPerGroup;
+    };
+    const int first = (int)threadIdx.x * per, last = first + per < a.batch ? first + per : a.batch;
+    int mine = 0;
+    for (int r = first; r < last; ++r) mine += groups_of(r);
+    const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane_ >= d) incl += up;
+    }
+    if (lane_ == 63) s_scan[wave_] = incl;
+    if (threadIdx.x == 0) s_scan[256] = -1;
+    __syncthreads();
+    int before = incl - mine;  // groups of the slices ahead of this thread's
+    for (int i = 0; i < wave_; ++i) before += s_scan[i];
+    if (target >= before && target < before + mine) {
+      int at = before;
+      for (int r = first; r < last; ++r) {
+        const int n = groups_of(r);
+        if (target < at + n) {
+          s_scan[256] = r;
+          s_scan[257] = n - 1 - (target - at);  // from the last group down
+          break;
+        }
+        at += n;
+      }
+    }
+    __syncthreads();
+    b = s_scan[256];
+    if (b < 0) return;  // past the last group
+    f0 = s_scan[257] * kWavesPerGroup;
+    __syncthreads();  // (the scan area is the packed-rows form's statistics area; nothing else uses it here)
+  }
+  const int64_t q_start = a.cu_seqlens_q[b];
+  int q_len, kv_len;
+  lengths_of(b, q_len, kv_len);
+  const int32_t* table = a.block_tables + (int64_t)b * a.max_blocks_per_seq;
   const int n_tok_tiles = (q_len + kRows - 1) / kRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
-  if (f0 >= n_wave_tiles) return;  // (the last n_splits workgroups of the row belong to the packed-rows form: f0 is past every tile there)
+  if (f0 >= n_wave_tiles) return;  // (cannot happen: the group was counted from these lengths)
   const int shift = kv_len - q_len;  // keys that precede the first new token
 
   const int lane = threadIdx.x & 63;

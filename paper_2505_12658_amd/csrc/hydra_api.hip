@@ -289,8 +289,16 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
     args.halves_per_split = (int32_t)((max_halves + splits - 1) / splits);
   }
   args.partials = static_cast<float*>(workspace);
-  if (groups + splits > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)(groups + splits), (unsigned)n_kv_heads, (unsigned)batch);
+  args.batch = batch;
+  // Workgroups of the wave-tile form: one per group of four wave tiles and KV head.  The request lengths are
+  // on the device, so this is an upper bound from the total: a request of q new tokens has at most
+  // (q / 32 + 1) * group / 4 + 1 groups.
+  int64_t tile_wgs = 0;
+  if (groups > 0) tile_wgs = (((int64_t)total_q / hydra::paged::kRows + batch) * args.group / hydra::paged::kWavesPerGroup + batch) * n_kv_heads;
+  const int64_t rows_wgs = (int64_t)batch * n_kv_heads * splits;
+  if (tile_wgs + rows_wgs > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  args.n_tile_wgs = (int32_t)tile_wgs;
+  const dim3 grid((unsigned)(tile_wgs + rows_wgs), 1, 1);
   const dim3 combine_grid((unsigned)n_kv_heads, (unsigned)batch);
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (head_dim) {

@@ -65,6 +65,21 @@ def test_ragged_hybrid_batches_full(case):
     _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
 
 
+def test_many_requests_with_scattered_chunks():
+    """More requests than the threads of a workgroup, with prefill chunks (ragged lengths, some shorter than a
+    wave tile, some invalid or empty requests) scattered among decode steps: the workgroups of the wave-tile
+    form locate their request by a scan over all requests, several per thread here."""
+    rng = np.random.default_rng(8)
+    n = 700
+    q_lens = [1] * n
+    kv_lens = rng.integers(1, 90, size=n).tolist()
+    for pos, ql, extra in ((0, 33, 0), (1, 200, 40), (255, 64, 64), (256, 5, 3), (257, 129, 1), (511, 6, 100), (512, 40, 0), (699, 300, 77), (300, 0, 9)):
+        q_lens[pos], kv_lens[pos] = ql, ql + extra
+    h = si.HybridBatch("many", q_lens, kv_lens, 8, 2, 64, seed=21)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
 def test_full_size_hybrid_batch():
     """The benchmark's hybrid batch (96 decode requests + 4 prefill chunks of 512, 28 / 4 heads of 128), whole output."""
     h = si.qwen2vl_hybrid()
