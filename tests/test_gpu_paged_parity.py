@@ -80,6 +80,28 @@ def test_many_requests_with_scattered_chunks():
     _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_hybrid_batches(seed):
+    """Seeded random hybrid batches: decode steps, short and long chunks, whole prefills, empty requests, in
+    random order, random head grouping, head_dim and block size; whole output against the oracle."""
+    rng = np.random.default_rng(2000 + seed)
+    hq, hkv = [(1, 1), (4, 1), (4, 2), (7, 1), (8, 8), (28, 4)][int(rng.integers(6))]
+    d = [64, 80, 128][int(rng.integers(3))]
+    bs = [1, 4, 16, 32][int(rng.integers(4))]
+    q_lens, kv_lens = [], []
+    for _ in range(int(rng.integers(1, 60))):
+        kind = int(rng.integers(5))
+        ql = [1, int(rng.integers(2, 9)), int(rng.integers(9, 200)), int(rng.integers(1, 150)), 0][kind]
+        extra = 0 if kind == 3 else int(rng.integers(0, 400))
+        q_lens.append(ql)
+        kv_lens.append(ql + extra if ql else int(rng.integers(0, 50)))
+    if sum(q_lens) == 0:
+        q_lens[0], kv_lens[0] = 3, 10
+    h = si.HybridBatch("random", q_lens, kv_lens, hq, hkv, d, block_size=bs, seed=seed)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
 def test_full_size_hybrid_batch():
     """The benchmark's hybrid batch (96 decode requests + 4 prefill chunks of 512, 28 / 4 heads of 128), whole output."""
     h = si.qwen2vl_hybrid()

@@ -248,6 +248,25 @@ def test_worklist_covers_every_tile_once_and_ends_with_cheap_items(hq, hkv, d, c
         assert all(a >= b for a, b in zip(t, t[1:])), (x, t)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_ragged_batches(seed):
+    """Seeded random batches (number of sequences, lengths with zeros and tile-boundary values mixed in, head
+    grouping, head_dim, mask) against the C oracle, whole output."""
+    rng = np.random.default_rng(1000 + seed)
+    hq, hkv = [(1, 1), (2, 1), (4, 2), (7, 1), (8, 8), (6, 3)][int(rng.integers(6))]
+    d = [64, 80, 128][int(rng.integers(3))]
+    causal = bool(rng.integers(2))
+    n = int(rng.integers(1, 40))
+    special = np.array([0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129])
+    lengths = np.where(rng.random(n) < 0.3, special[rng.integers(len(special), size=n)], rng.integers(0, 600, size=n)).tolist()
+    if sum(lengths) == 0:
+        lengths[0] = 5
+    w = si.custom(lengths, hq, hkv, d, causal, seed=seed)
+    q, k, v = si.make_qkv(w)
+    out = _run_gpu(w, q, k, v)
+    _check(out, c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, causal, w.softmax_scale))
+
+
 def test_many_short_sequences():
     """More sequences than the work-list builder keeps in LDS (4096): exercises its global-memory path,
     queue rows beyond one wave, and zero-length sequences in between."""
