@@ -426,20 +426,24 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
 
 #endif  // __HIP_DEVICE_COMPILE__
 
-// grid = n_tile_wgs + batch * n_kv_heads * n_splits workgroups, one-dimensional.
-//   - The first n_tile_wgs workgroups run the wave-tile form: workgroup w serves KV head w % n_kv_heads and group
+// grid = batch * n_kv_heads * n_splits + n_tile_wgs workgroups, one-dimensional.
+//   - The first batch * n_kv_heads * n_splits run the packed-rows form (decode steps, chunks of a few tokens):
+//     n_splits workgroups per (request, KV head), each a share of the context; requests of the other form are
+//     left at once.
+//   - The last n_tile_wgs run the wave-tile form: workgroup w of them serves KV head w % n_kv_heads and group
 //     number w / n_kv_heads in the list of all groups of four wave tiles of all requests that take this form
 //     (q_len * group > 32), which it finds for itself: the 256 threads add up the groups of a slice of the
-//     requests each, a scan over the slices gives the request, the remainder the group.  The host sizes
-//     n_tile_wgs from the total number of new tokens (it cannot see the lengths); workgroups past the last
-//     group leave at once.  Inside a request the groups are taken from the last token tile down, which see
-//     the most keys.
-//   - The others run the packed-rows form (decode steps, chunks of a few tokens): n_splits workgroups per
-//     (request, KV head), each a share of the context; requests of the other form are left at once.
-// The hardware starts workgroups in index order, so the long workgroups of a batch (prefill chunks) are all under
-// way before the short ones (decode steps) take what is left of the chip.  (A grid with one row of workgroups
-// per request made every decode request pay for the widest chunk's row: ten thousand workgroups that only
-// looked at their request's length and left, and a chunk that stood last in the batch started last.)
+//     requests each and a scan over the slices gives every request's place; the requests of this form (few:
+//     prefill chunks) are then ranked by context length in LDS and the groups counted off in that order, the
+//     longest context first and inside a request from the last token tile down (which sees the most keys).
+//     The host sizes n_tile_wgs from the total number of new tokens (it cannot see the lengths); workgroups past
+//     the last group leave at once.
+// The hardware starts workgroups in index order.  Measured on the hybrid benchmark batch (96 decode steps, 4
+// chunks): decode steps first and then the chunks' workgroups from the longest down, 82 us; chunks first in
+// batch order, 88 us (the decode steps then wait for the few free slots and the long ones among them end the
+// kernel); a grid with one row of workgroups per request (which made every decode request pay for the widest
+// chunk's row with workgroups that only looked at its length and left, and started a chunk that stood last in the
+// batch last), 95 us.
 // Both forms live in one kernel so that the decode requests and the prefill chunks of a batch run side by
 // side on the chip; two workgroups per compute unit (a wave keeps within 256 registers, a workgroup within
 // half of the LDS).
@@ -460,8 +464,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (q_len < 0 || kv_len < q_len) q_len = 0;
   };
   int b, kv_head, f0 = 0;
-  if ((int)blockIdx.x >= a.n_tile_wgs) {
-    const int r = (int)blockIdx.x - a.n_tile_wgs;
+  const int n_rows_wgs = (int)gridDim.x - a.n_tile_wgs;
+  if ((int)blockIdx.x < n_rows_wgs) {
+    const int r = (int)blockIdx.x;
     const int pair = r / a.n_splits, split = r - pair * a.n_splits;
     b = pair / a.n_kv_heads;
     kv_head = pair - b * a.n_kv_heads;
@@ -473,38 +478,95 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
   {
     // which group of which request: see above.  Thread i adds up requests [i * per, (i + 1) * per).
-    int* s_scan = reinterpret_cast<int*>(s_stats);  // [0..3] the waves' sums, [256] = request, [257] = group
-    const int target = (int)blockIdx.x / a.n_kv_heads;
-    kv_head = (int)blockIdx.x - target * a.n_kv_heads;
+    int* s_scan = reinterpret_cast<int*>(s_stats);  // [0..3] the waves' groups, [4..7] the waves' requests, [256] = request, [257] = group
+    const int target = ((int)blockIdx.x - n_rows_wgs) / a.n_kv_heads;
+    kv_head = ((int)blockIdx.x - n_rows_wgs) - target * a.n_kv_heads;
     const int per = (a.batch + 255) / 256;
-    auto groups_of = [&](int r) {
-      int q_len, kv_len;
+    auto groups_of = [&](int r, int& kv_len) {
+      int q_len;
       lengths_of(r, q_len, kv_len);
       if (q_len * a.group <= kRows) return 0;
       return (((q_len + kRows - 1) / kRows) * a.group + kWavesPerGroup - 1) / kWavesPerGroup;
     };
     const int first = (int)threadIdx.x * per, last = first + per < a.batch ? first + per : a.batch;
-    int mine = 0;
-    for (int r = first; r < last; ++r) mine += groups_of(r);
+    int mine = 0, mine_reqs = 0;  // groups, and requests that have groups, in this thread's slice
+    for (int r = first; r < last; ++r) {
+      int kv;
+      const int n = groups_of(r, kv);
+      mine += n;
+      mine_reqs += n > 0 ? 1 : 0;
+    }
     const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
-    int incl = mine;
+    int incl = mine, incl_reqs = mine_reqs;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-      const int up = __shfl_up(incl, d);
-      if (lane_ >= d) incl += up;
+      const int up = __shfl_up(incl, d), up_reqs = __shfl_up(incl_reqs, d);
+      if (lane_ >= d) {
+        incl += up;
+        incl_reqs += up_reqs;
+      }
     }
-    if (lane_ == 63) s_scan[wave_] = incl;
+    if (lane_ == 63) {
+      s_scan[wave_] = incl;
+      s_scan[4 + wave_] = incl_reqs;
+    }
     if (threadIdx.x == 0) s_scan[256] = -1;
     __syncthreads();
-    int before = incl - mine;  // groups of the slices ahead of this thread's
-    for (int i = 0; i < wave_; ++i) before += s_scan[i];
-    if (target >= before && target < before + mine) {
+    int before = incl - mine, before_reqs = incl_reqs - mine_reqs;  // of the slices ahead of this thread's
+    for (int i = 0; i < wave_; ++i) {
+      before += s_scan[i];
+      before_reqs += s_scan[4 + i];
+    }
+    const int total_reqs = s_scan[4] + s_scan[5] + s_scan[6] + s_scan[7];
+    if (target >= s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3]) return;  // past the last group
+    // Requests with the longest contexts first: their workgroups run longest, and the kernel is as long as the
+    // last of them.  The requests of this form (few: prefill chunks) are gathered in LDS, ranked by context
+    // length, and the groups are counted off in that order.  (More than kMaxSorted of them: batch order.)
+    constexpr int kMaxSorted = 256;
+    if (total_reqs <= kMaxSorted) {
+      int* s_req = reinterpret_cast<int*>(smem);  // the tile stages are not in use yet
+      int* s_groups = s_req + kMaxSorted, *s_key = s_req + 2 * kMaxSorted;
+      int* s_sorted_req = s_req + 3 * kMaxSorted, *s_sorted_groups = s_req + 4 * kMaxSorted;
+      int k = before_reqs;
+      for (int r = first; r < last; ++r) {
+        int kv;
+        const int n = groups_of(r, kv);
+        if (n > 0) {
+          s_req[k] = r;
+          s_groups[k] = n;
+          s_key[k] = kv;
+          ++k;
+        }
+      }
+      __syncthreads();
+      if ((int)threadIdx.x < total_reqs) {
+        const int key = s_key[threadIdx.x];
+        int rank = 0;
+        for (int j = 0; j < total_reqs; ++j) rank += (s_key[j] > key || (s_key[j] == key && j < (int)threadIdx.x)) ? 1 : 0;
+        s_sorted_req[rank] = s_req[threadIdx.x];
+        s_sorted_groups[rank] = s_groups[threadIdx.x];
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int at = 0;
+        for (int e = 0; e < total_reqs; ++e) {
+          const int n = s_sorted_groups[e];
+          if (target < at + n) {
+            s_scan[256] = s_sorted_req[e];
+            s_scan[257] = n - 1 - (target - at);  // from the last group down
+            break;
+          }
+          at += n;
+        }
+      }
+    } else if (target >= before && target < before + mine) {
       int at = before;
       for (int r = first; r < last; ++r) {
-        const int n = groups_of(r);
+        int kv;
+        const int n = groups_of(r, kv);
         if (target < at + n) {
           s_scan[256] = r;
-          s_scan[257] = n - 1 - (target - at);  // from the last group down
+          s_scan[257] = n - 1 - (target - at);
           break;
         }
         at += n;
@@ -512,9 +574,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     __syncthreads();
     b = s_scan[256];
-    if (b < 0) return;  // past the last group
+    if (b < 0) return;  // (cannot happen: the target was below the total)
     f0 = s_scan[257] * kWavesPerGroup;
-    __syncthreads();  // (the scan area is the packed-rows form's statistics area; nothing else uses it here)
+    __syncthreads();  // (the scan area is the packed-rows form's statistics area, the lists lie in the tile stages)
   }
   const int64_t q_start = a.cu_seqlens_q[b];
   int q_len, kv_len;
