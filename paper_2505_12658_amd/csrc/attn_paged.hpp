@@ -58,7 +58,7 @@ struct PagedArgs {
   int32_t halves_per_split;
   float* partials;  // [batch, n_kv_heads, n_splits] records of kPartialFloats<D> floats
   int32_t batch;
-  int32_t n_tile_wgs;  // workgroups of the wave-tile form at the front of the grid (an upper bound from the host)
+  int32_t n_tile_wgs;  // workgroups of the wave-tile form at the end of the grid (an upper bound from the host)
 };
 
 // One partial result of the packed-rows form: per row (32 rows) the maximum and the sum, then the
