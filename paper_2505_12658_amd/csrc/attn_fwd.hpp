@@ -648,11 +648,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     constexpr bool NEXT_QK = decltype(next_qk_tag)::value;
     constexpr int NMS = QK ? NM : QS * NP;       // matrix instructions of this step
     if (needs_mask(j)) apply_mask(j, Sc);
-    float psum[QS];
-#pragma unroll
-    for (int qs = 0; qs < QS; ++qs) psum[qs] = 0.f;
-    // vector work piece i of this step: one softmax pair
-    auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_pair(i, Sc, Pc, psum); };
+    // vector work piece i of this step: one softmax pair (its exponentials go straight onto the row sum)
+    auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_pair(i, Sc, Pc, row_sum); };
     bf16x8_t kf_cur = fr.k0, kf_nxt = fr.k1, vf_cur = fr.v0, vf_nxt = fr.v1, kf_nn, vf_nn;
     int ms = 0;  // matrix-instruction index inside the step
     auto shadow = [&](int ms_done) __attribute__((always_inline)) {
@@ -690,11 +687,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
         vf_cur = vf_nxt;
         vf_nxt = vf_nn;
       }
-    }
-#pragma unroll
-    for (int qs = 0; qs < QS; ++qs) {
-      row_sum[qs] += psum[qs];
-      asm volatile("" : "+v"(row_sum[qs]));
     }
     if constexpr (NEXT_RB >= 0) {
       fr.k0 = kf_cur;
