@@ -112,9 +112,9 @@ struct TileGeom {
   // D = 80: the third 32-column block of P V has 16 columns to spare.  The lanes that feed them read bf16 ones
   // from a constant area instead of the V tile, so the matrix unit delivers the softmax row sums in output
   // columns 80..95 and the vector unit does not have to add them up (16 additions per key block and wave).
-  // The area covers every offset a V fragment read adds to its lane address.
+  // The area covers every offset a V fragment read adds to its lane address (ring slot, key block, step).
   static constexpr bool kSumsFromMatrixUnit = D == 80;
-  static constexpr int kOnesBytes = kSumsFromMatrixUnit ? 9 * 1024 : 0;
+  static constexpr int kOnesBytes = kSumsFromMatrixUnit ? (kRing - 1) * kTileBytes + 9 * 1024 : 0;
   static constexpr int kOnesAt = 2 * kRing * kTileBytes + 64;    // (+ slack behind the last V tile)
   static constexpr int kLdsBytes = kOnesAt + kOnesBytes;
 };
@@ -368,7 +368,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
   __shared__ __attribute__((aligned(16))) int s_claim[8];
   if constexpr (G::kSumsFromMatrixUnit) {
-    static_assert(kKvTileRows * ROWB - 8 * ROWB + 8 <= G::kOnesBytes, "a V fragment read stays inside the ones");
+    static_assert((R - 1) * G::kTileBytes + kKvTileRows * ROWB - 8 * ROWB + 8 <= G::kOnesBytes, "a V fragment read stays inside the ones");
     for (int i = threadIdx.x * 16; i < G::kOnesBytes; i += 256 * 16)
       *reinterpret_cast<u32x4_t*>(HYDRA_LDS_BYTE(k_ring + G::kOnesAt + i)) = u32x4_t{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
   }
@@ -540,21 +540,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc) {
       const int chunk = 4 * cc + 2 * grp + ((sl & 3) >> 1);
-      // V tile "-1": the first advance brings it to tile 0
-      v_addr[cc] = lds_base + (R - 1) * G::kTileBytes + R * G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);
+      v_addr[cc] = lds_base + R * G::kTileBytes + r * ROWB + v_swizzle<D>(r, chunk) * 16 + 8 * (sl & 1);  // V ring, slot 0
     }
     if constexpr (G::kSumsFromMatrixUnit) {
-      // columns 80..95 (the upper 16 of the last block): ones, wherever the tile is
+      // columns 80..95 (the upper 16 of the last block): ones (the area is long enough for either ring slot)
       if (grp == 1) v_addr[CC - 1] = lds_base + G::kOnesAt;
     }
   }
-  auto advance_addresses = [&](int t) {  // to K tile t, V tile t - 1
-    const int dk = (t % R == 0) ? -(R - 1) * G::kTileBytes : G::kTileBytes;
-    const int dv = ((t - 1) % R == 0) ? -(R - 1) * G::kTileBytes : G::kTileBytes;
+  // The address registers point at slot 0 of both rings from here through the hot loop, whose reads name
+  // their ring slot in the instruction offset (two iterations per trip: the slots are constants there).  The
+  // iterations after the hot loop move the registers instead (position_addresses) and read at offset 0.
+  int k_pos = 0, v_pos = 0;  // where the registers point: bytes from slot 0
+  auto position_addresses = [&](int t) {  // to K tile t, V tile t - 1 (t >= 1)
+    const int k_new = (t % R) * G::kTileBytes, v_new = ((t - 1) % R) * G::kTileBytes;
+    const int dk = k_new - k_pos, dv = v_new - v_pos;
 #pragma unroll
     for (int s = 0; s < KS; ++s) k_addr[s] += dk;
 #pragma unroll
-    for (int cc = 0; cc < CC; ++cc) v_addr[cc] += (G::kSumsFromMatrixUnit && cc == CC - 1 && grp == 1) ? 0 : dv;
+    for (int cc = 0; cc < CC; ++cc) v_addr[cc] += dv;
+    k_pos = k_new;
+    v_pos = v_new;
   };
 
   f32x16_t o_acc[QS][CC];
@@ -579,13 +584,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   for (int qs = 0; qs < QS; ++qs) row_sum[qs] = 0.f;
 
   // LDS fragment reads; rb = key block inside the tile the address registers point at.
-  auto load_k_frag = [&](int rb, int s) -> bf16x8_t {
-    return *reinterpret_cast<const bf16x8_t*>(HYDRA_LDS_BYTE(k_addr[s] + rb * kKeyBlock * ROWB));
+  // (koff / voff: ring slot of the tile, in bytes; constants where it matters, so they end up in the instruction)
+  auto load_k_frag = [&](int rb, int s, int koff) -> bf16x8_t {
+    return *reinterpret_cast<const bf16x8_t*>(HYDRA_LDS_BYTE(k_addr[s] + koff + rb * kKeyBlock * ROWB));
   };
   // PV unit u = (s2, cc): the V^T fragment of 16 keys x 32 columns
-  auto load_v_frag = [&](int rb, int u) -> bf16x8_t {
+  auto load_v_frag = [&](int rb, int u, int voff) -> bf16x8_t {
     const int cc = u % CC, s2 = u / CC;
-    const uint32_t at = v_addr[cc] + rb * kKeyBlock * ROWB + s2 * 16 * ROWB;
+    const uint32_t at = v_addr[cc] + voff + rb * kKeyBlock * ROWB + s2 * 16 * ROWB;
     const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_BYTE(at));
     const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)HYDRA_LDS_BYTE(at + 8 * ROWB));
     typedef __attribute__((ext_vector_type(8))) short s16x8_t;
@@ -641,7 +647,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // fragments into `fr` (next_qk_tag: whether it has QK units).  next_tag < 0: nothing is fetched ahead
   // (the next tiles are only complete after the iteration's barrier; the caller fetches them then).
   auto block_step = [&](auto rb_tag, auto qk_tag, auto next_tag, auto next_qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS],
-                        const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2], StepFrags& fr) __attribute__((always_inline)) {
+                        const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2], StepFrags& fr, int koff, int voff) __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
     constexpr bool QK = decltype(qk_tag)::value;
     constexpr int NEXT_RB = decltype(next_tag)::value;
@@ -664,8 +670,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 #pragma unroll
     for (int u = 0; u <= NP; ++u) {
       if (QK && u < NQ) {
-        if (u + 2 < NQ) kf_nn = load_k_frag(RB, u + 2);
-        else if (NEXT_RB >= 0 && NEXT_QK && u + 2 - NQ < NQ) kf_nn = load_k_frag(NEXT_RB, u + 2 - NQ);
+        if (u + 2 < NQ) kf_nn = load_k_frag(RB, u + 2, koff);
+        else if (NEXT_RB >= 0 && NEXT_QK && u + 2 - NQ < NQ) kf_nn = load_k_frag(NEXT_RB, u + 2 - NQ, koff);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
           if (u == 0) mfma_qk_init(Sn[qs], neg_ref[qs], kf_cur, qf[qs][u]); else mfma_qk_acc(Sn[qs], kf_cur, qf[qs][u]);
@@ -676,8 +682,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       }
       if (u >= 1) {
         const int pu = u - 1;
-        if (pu + 2 < NP) vf_nn = load_v_frag(RB, pu + 2);
-        else if (NEXT_RB >= 0) vf_nn = load_v_frag(NEXT_RB, pu + 2 - NP);
+        if (pu + 2 < NP) vf_nn = load_v_frag(RB, pu + 2, voff);
+        else if (NEXT_RB >= 0) vf_nn = load_v_frag(NEXT_RB, pu + 2 - NP, voff);
         const int cc = pu % CC, s2 = pu / CC;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
@@ -696,11 +702,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
   };
   // first fragments of a step that reads key block rb of the tiles the address registers point at
-  auto fetch_step_frags = [&](int rb, bool with_qk, StepFrags& fr) __attribute__((always_inline)) {
-    fr.v0 = load_v_frag(rb, 0);
-    if (with_qk) fr.k0 = load_k_frag(rb, 0);
-    fr.v1 = load_v_frag(rb, 1);
-    if (with_qk) fr.k1 = load_k_frag(rb, 1);
+  auto fetch_step_frags = [&](int rb, bool with_qk, StepFrags& fr, int koff, int voff) __attribute__((always_inline)) {
+    fr.v0 = load_v_frag(rb, 0, voff);
+    if (with_qk) fr.k0 = load_k_frag(rb, 0, koff);
+    fr.v1 = load_v_frag(rb, 1, voff);
+    if (with_qk) fr.k1 = load_k_frag(rb, 1, koff);
   };
 
   // PV only (after this wave's last softmax): O += V^T P for key block rb of the V tile in reach
@@ -709,7 +715,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     // fetches each one right before its use and the wave sits through the LDS latency NP times)
     bf16x8_t vf[NP];
 #pragma unroll
-    for (int u = 0; u < NP; ++u) vf[u] = load_v_frag(rb, u);
+    for (int u = 0; u < NP; ++u) vf[u] = load_v_frag(rb, u, 0);
     HYDRA_SCHED_FENCE();
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
@@ -740,7 +746,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     // with scheduling fences in between: see pv_only)
     bf16x8_t kf0[NQ], kf1[NQ];
 #pragma unroll
-    for (int s = 0; s < NQ; ++s) kf0[s] = load_k_frag(0, s);
+    for (int s = 0; s < NQ; ++s) kf0[s] = load_k_frag(0, s, 0);
     HYDRA_SCHED_FENCE();
 #pragma unroll
     for (int s = 0; s < NQ; ++s) {
@@ -751,7 +757,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     }
     HYDRA_SCHED_FENCE();
 #pragma unroll
-    for (int s = 0; s < NQ; ++s) kf1[s] = load_k_frag(1, s);
+    for (int s = 0; s < NQ; ++s) kf1[s] = load_k_frag(1, s, 0);
     HYDRA_SCHED_FENCE();
     s_results_to_valu(s_a);
     if (needs_mask(0)) apply_mask(0, s_a);
@@ -824,36 +830,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // Inside its pipeline steps a wave goes ahead of the SIMD's other wave when that one is between items
   // (Q scaling, epilogue: long runs of vector instructions that would otherwise take every other issue slot).
   __builtin_amdgcn_s_setprio(1);
-  for (; t <= F_loop; ++t) {
-    advance_addresses(t);
-    fetch_step_frags(0, true, fr);
+  // Iteration t reads K tile t (ring slot t % 2) and V tile t - 1 (slot (t - 1) % 2); t is odd at the top of a trip.
+  static_assert(R == 2, "two iterations per trip cover the ring");
+  auto hot_iteration = [&](int tt, int koff, int voff) __attribute__((always_inline)) {
+    fetch_step_frags(0, true, fr, koff, voff);
     HYDRA_SCHED_FENCE();
-    issue_loads(t);
-    block_step(RB0{}, WithQK{}, NextRB<1>{}, WithQK{}, 2 * t - 1, s_b, s_a, p_a, p_b, fr);
-    block_step(RB1{}, WithQK{}, NextRB<-1>{}, WithQK{}, 2 * t, s_a, s_b, p_b, p_a, fr);
+    issue_loads(tt);
+    block_step(RB0{}, WithQK{}, NextRB<1>{}, WithQK{}, 2 * tt - 1, s_b, s_a, p_a, p_b, fr, koff, voff);
+    block_step(RB1{}, WithQK{}, NextRB<-1>{}, WithQK{}, 2 * tt, s_a, s_b, p_b, p_a, fr, koff, voff);
     wait_all_loads();
     __syncthreads();
+  };
+  for (; t + 1 <= F_loop; t += 2) {
+    hot_iteration(t, G::kTileBytes, 0);
+    hot_iteration(t + 1, 0, G::kTileBytes);
+  }
+  if (t <= F_loop) {
+    hot_iteration(t, G::kTileBytes, 0);
+    ++t;
   }
   if (!odd_steps && F > 0) {
-    advance_addresses(t);
-    fetch_step_frags(0, true, fr);
+    position_addresses(t);
+    fetch_step_frags(0, true, fr, 0, 0);
     HYDRA_SCHED_FENCE();
     issue_loads(t);
-    block_step(RB0{}, WithQK{}, NextRB<1>{}, LastStep{}, 2 * t - 1, s_b, s_a, p_a, p_b, fr);
-    block_step(RB1{}, LastStep{}, NextRB<-1>{}, LastStep{}, 2 * t, s_a, s_b, p_b, p_a, fr);
+    block_step(RB0{}, WithQK{}, NextRB<1>{}, LastStep{}, 2 * t - 1, s_b, s_a, p_a, p_b, fr, 0, 0);
+    block_step(RB1{}, LastStep{}, NextRB<-1>{}, LastStep{}, 2 * t, s_a, s_b, p_b, p_a, fr, 0, 0);
     wait_all_loads();
     __syncthreads();
     ++t;
   }
   if (NB > 0 && t <= W) {
-    advance_addresses(t);
+    position_addresses(t);
     if (odd_steps) {
-      fetch_step_frags(0, false, fr);
+      fetch_step_frags(0, false, fr, 0, 0);
       HYDRA_SCHED_FENCE();
     }
     issue_loads(t);
     if (odd_steps) {
-      block_step(RB0{}, LastStep{}, NextRB<-1>{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b, fr);  // NB - 1 = 2t - 1
+      block_step(RB0{}, LastStep{}, NextRB<-1>{}, LastStep{}, NB - 1, s_b, s_a, p_a, p_b, fr, 0, 0);  // NB - 1 = 2t - 1
       pv_only(1, p_b);                                            // V block NB - 1 = 2t - 1: second block of V tile t - 1
     } else {
       pv_only(0, p_a);  // V block NB - 1 = 2t - 2: first block of V tile t - 1
