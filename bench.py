@@ -179,7 +179,7 @@ def cpu_baseline(w: si.Workload, host_qkv, budget_s: float = 15.0):
 
 def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode", prefill: str = HEADLINE):
     """The paper runs the vision encoder and the language model of one instance on two streams
-    (Section 4.3).  Here: encode attention steps on one stream and prefill steps (attention + KV scatter)
+    (Section 4.2, the paragraph on dual-stream parallelism; measured in Section 5.5).  Here: encode attention steps on one stream and prefill steps (attention + KV scatter)
     on another, launched together, against the same steps launched one after the other."""
     we, wp = si.WORKLOADS[encode](), si.WORKLOADS[prefill]()
     be, bp = DeviceBatch(we, n_sets, dev), DeviceBatch(wp, n_sets, dev)
@@ -212,7 +212,7 @@ def dual_stream(dev, n_sets: int, steps: int, encode: str = "qwen2vl_vit_encode"
 
 
 def encode_beside_decode(dev, be: DeviceBatch, se, sd, n_sets: int, steps: int, n_requests: int = 256, kv_len: int = 1024):
-    """The pairing the paper's two-stream experiment uses (Section 5: encode beside decode, context length 1024):
+    """The pairing the paper's two-stream experiment uses (Section 5.5: encode beside decode, context length 1024):
     encode attention (matrix-bound) on one stream, decode attention over the paged cache (memory-bound) on the
     other, as many decode launches per encode launch as take about the same time.  Three ways: one after the
     other; launched together with the encode kernel at its own size (its persistent workgroups hold every

@@ -109,9 +109,10 @@ int hydra_attn_varlen_fwd_prebuilt(const void* q, const void* k, const void* v, 
 
 /*
  * hydra_attn_varlen_fwd_prebuilt for an instance that runs its vision encoder and its language model
- * on two streams at once (Section 4.3).  The attention kernel is made of persistent workgroups that
- * by default take every compute unit's registers whole, so a kernel launched beside it on another
- * stream only gets the compute units as they drain.  Here the caller says how many persistent
+ * on two streams at once (Section 4.2, dual-stream parallelism; measured in Section 5.5).  The
+ * attention kernel is made of persistent workgroups that by default take every compute unit's
+ * registers whole, so a kernel launched beside it on another stream only gets the compute units
+ * as they drain.  Here the caller says how many persistent
  * workgroups per compute unit the kernel may start:
  *
  *   workgroups_per_cu  >= 1 (otherwise HYDRA_ERR_INVALID_ARG); values above the kernel's own number
@@ -156,7 +157,7 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
  *
  * The paper's batch scheduler (Algorithm 1) fills one batch, under a token budget, with the decode
  * requests (one new token each) and with chunks of prefill requests (get_chunked_size tokens each);
- * every one of them attends to its request's KV cache, which is paged (Section 5, block size 16 in
+ * every one of them attends to its request's KV cache, which is paged (Section 4.5, block size 16 in
  * Section 5.1).  Request b brings q_len = cu_seqlens_q[b+1] - cu_seqlens_q[b] new tokens and has
  * kv_lens[b] tokens of context in the cache, the new tokens included (their K/V are written first,
  * with hydra_kv_cache_write).  For new token i, query head h (KV head hk as above):
@@ -206,9 +207,9 @@ size_t hydra_attn_paged_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32
 /*
  * Paged image cache: the vision encoder's output rows into cache pages, and back out of them.
  *
- * The paper keeps the image tokens that the encode stage produces in an image cache managed in pages
- * like the KV cache (Section 5; image-cache block size 576 in Section 5.1), so that a request can move
- * to another instance with its page table and repeated images can be reused.  The caller flattens an
+ * The encode stage's output tokens live in an image cache that is organised in fixed-size pages, the
+ * same scheme as the KV cache (Section 4.5; image-cache block size 576 in Section 5.1); a request then
+ * migrates to another instance by its page table, and an image seen before is served from its pages.  The caller flattens an
  * image's page table into one slot per row, slot = page_id * page_rows + row_in_page.
  *
  *   hydra_page_cache_write :  for t in [0, n_rows): s = slot_mapping[t]; if s >= 0: cache[s, :] = rows[t, :]

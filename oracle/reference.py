@@ -132,7 +132,7 @@ def attn_paged(q, k_cache, v_cache, block_tables, cu_seqlens_q, kv_lens, scale: 
 
     What is computed: the batch that the paper's Algorithm 1 assembles holds decode requests (one
     new token) and chunks of prefill requests (get_chunked_size new tokens); each attends to its
-    own KV cache, kept in pages (Section 5: paged attention; block size 16 in Section 5.1).  Request
+    own KV cache, kept in pages (Section 4.5: paged attention; block size 16 in Section 5.1).  Request
     b has q_len = cu_seqlens_q[b+1] - cu_seqlens_q[b] new tokens and kv_lens[b] tokens of context
     in the cache, the new ones included.  Reading taken (the paper does not spell the mask out):
     the new tokens are the LAST q_len positions of the context and attention is causal, so new
@@ -223,7 +223,7 @@ def kv_cache_write(k_bits, v_bits, k_cache_bits, v_cache_bits, slot_mapping, blo
 def page_cache_write(rows_bits, cache_bits, slot_mapping):
     """Paged image cache, write direction, on raw bf16 bit patterns: returns the new cache.
 
-    The paper pages the image cache like the KV cache (Section 5; block size 576 in Section 5.1).
+    The paper pages the image cache like the KV cache (Section 4.5; block size 576 in Section 5.1).
     rows_bits: [n, row_elems]; cache_bits: [num_slots, row_elems] (pages flattened); slot_mapping: [n].
     Rows are taken in order; slot < 0 skips the row; every other cache row keeps its old value."""
     cache = np.array(cache_bits, dtype=np.uint16, copy=True)

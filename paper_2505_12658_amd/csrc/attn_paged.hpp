@@ -2,7 +2,7 @@
 //
 // The paper's batch scheduler (Algorithm 1) fills one batch, under a token budget, with the decode
 // requests (one new token each) and with chunks of prefill requests (get_chunked_size new tokens
-// each); all of them attend to their request's KV cache, which is paged (Section 5, block size 16).
+// each); all of them attend to their request's KV cache, which is paged (Section 4.5; block size 16 in Section 5.1).
 // Request b brings q_len new tokens and has kv_len tokens of context in the cache, the new ones
 // included (written beforehand by the paged KV write).  New token i sees keys 0 .. kv_len - q_len + i:
 // the causal mask aligned to the END of the context.  q_len == kv_len is an ordinary prefill,

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <tuple>
+
 #include "../../include/hydra_attn.h"
 #include "attn_careful.hpp"
 #include "attn_fwd.hpp"
@@ -17,6 +19,20 @@ namespace {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool head_dim_supported(int d) { return d == 64 || d == 80 || d == 128; }
+
+// Enqueues one kernel and returns the status of THIS launch (the runtime's sticky last-error slot
+// is shared by every caller of the process and may hold somebody else's failure).
+template <typename... Params, typename... Args>
+hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, const Args&... args) {
+  static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+  std::tuple<Params...> vals(args...);
+  return std::apply(
+      [&](auto&... v) {
+        void* ptrs[] = {static_cast<void*>(&v)...};
+        return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+      },
+      vals);
+}
 
 // Compute units of the current device (0 if the runtime cannot tell).  Looked up on every call:
 // the library keeps no state, and the attribute query does not touch the device.
@@ -39,14 +55,15 @@ hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned comput
                                                                                                   : (unsigned)hydra::kWorkgroupsPerCu<D>;
   const unsigned grid = per_cu * compute_units;
   const unsigned careful_grid = compute_units;
+  hipError_t err;
   if (causal) {
-    hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, true>), dim3(grid), dim3(256), 0, stream, args);
-    hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, true>), dim3(careful_grid), dim3(256), 0, stream, args);
+    err = launch(hydra::attn_fwd_kernel<D, true>, dim3(grid), dim3(256), stream, args);
+    if (err == hipSuccess) err = launch(hydra::careful::attn_fwd_careful_kernel<D, true>, dim3(careful_grid), dim3(256), stream, args);
   } else {
-    hipLaunchKernelGGL((hydra::attn_fwd_kernel<D, false>), dim3(grid), dim3(256), 0, stream, args);
-    hipLaunchKernelGGL((hydra::careful::attn_fwd_careful_kernel<D, false>), dim3(careful_grid), dim3(256), 0, stream, args);
+    err = launch(hydra::attn_fwd_kernel<D, false>, dim3(grid), dim3(256), stream, args);
+    if (err == hipSuccess) err = launch(hydra::careful::attn_fwd_careful_kernel<D, false>, dim3(careful_grid), dim3(256), stream, args);
   }
-  return hipGetLastError();
+  return err;
 }
 
 // Bytes of one partial result of the paged kernel's packed-rows form.
@@ -132,25 +149,32 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
   int32_t* flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   const int group = n_q_heads / n_kv_heads;
   const int tail_items = hydra::tail_sort_items(group, head_dim);
-  if (causal)
-    hipLaunchKernelGGL(hydra::build_worklist_kernel<true>, dim3(hydra::prepass_workgroups(lay.capacity)), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
-  else
-    hipLaunchKernelGGL(hydra::build_worklist_kernel<false>, dim3(hydra::prepass_workgroups(lay.capacity)), dim3(hydra::kPrepassThreads), 0, s, cu_seqlens, batch, n_kv_heads,
-                       group, ctrl, sorted_seq, queue_prefix, (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
-  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+  const dim3 grid(hydra::prepass_workgroups(lay.capacity)), block(hydra::kPrepassThreads);
+  const hipError_t err =
+      causal ? launch(hydra::build_worklist_kernel<true>, grid, block, s, cu_seqlens, batch, n_kv_heads, group, ctrl, sorted_seq, queue_prefix,
+                      (int)lay.rows, items, flags, (int)lay.capacity, tail_items)
+             : launch(hydra::build_worklist_kernel<false>, grid, block, s, cu_seqlens, batch, n_kv_heads, group, ctrl, sorted_seq, queue_prefix,
+                      (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
+  return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 namespace {
 
-// The attention launch against a prebuilt work list; workgroups_per_cu == 0: the kernel's own number.
-int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
-                  int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
-                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
-                  size_t workspace_bytes, int32_t workgroups_per_cu, void* stream) {
+// Every host-side check of an attention call (sizes, pointers, strides, 32-bit addressing limits, the
+// workspace, the device), shared by the entry points so that each of them has finished checking
+// before its first launch.  *done is set when the call has nothing to do; *cus receives the number of
+// compute units.
+int validate_attn_call(const void* q, const void* k, const void* v, const void* out, int64_t q_token_stride, int64_t k_token_stride,
+                       int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale, const void* workspace,
+                       size_t workspace_bytes, bool* done, unsigned* cus) {
+  *done = false;
   if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
-  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
+  if (batch == 0 || total_tokens == 0) {
+    *done = true;
+    return HYDRA_OK;
+  }
   if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
   if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
@@ -162,8 +186,24 @@ int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_
     const int64_t widest = k_token_stride > v_token_stride ? k_token_stride : v_token_stride;
     if (((int64_t)max_seqlen + 2 * hydra::kKvTileRows) * widest * 2 >= ((int64_t)1 << 31)) return HYDRA_ERR_UNSUPPORTED;
   }
+  if (int rc = check_workspace(workspace, workspace_bytes, hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads))) return rc;
+  *cus = compute_units();
+  if (*cus == 0) return HYDRA_ERR_LAUNCH;
+  return HYDRA_OK;
+}
+
+// The attention launch against a prebuilt work list; workgroups_per_cu == 0: the kernel's own number.
+int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
+                  int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
+                  size_t workspace_bytes, int32_t workgroups_per_cu, void* stream) {
+  bool done = false;
+  unsigned grid = 0;
+  if (int rc = validate_attn_call(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                                  n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, &done, &grid))
+    return rc;
+  if (done) return HYDRA_OK;
   const hydra::WorkspaceLayout lay = hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads);
-  if (int rc = check_workspace(workspace, workspace_bytes, lay)) return rc;
 
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   hydra::AttnArgs args;
@@ -185,8 +225,6 @@ int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   args.scale_log2 = scale_log2 > 1e-30f ? scale_log2 : 1e-30f;
 
-  const unsigned grid = compute_units();
-  if (grid == 0) return HYDRA_ERR_LAUNCH;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err;
   switch (head_dim) {
@@ -221,17 +259,13 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
                           int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
                           int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal, float softmax_scale, void* workspace,
                           size_t workspace_bytes, void* stream) {
-  // validate everything before the first launch, so that an error never leaves half the work enqueued
-  if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
-  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return HYDRA_ERR_INVALID_ARG;
-  if (batch == 0 || total_tokens == 0) return HYDRA_OK;
-  if (!q || !k || !v || !out || !cu_seqlens) return HYDRA_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HYDRA_ERR_INVALID_ARG;
-  if (q_token_stride < (int64_t)n_q_heads * head_dim || k_token_stride < (int64_t)n_kv_heads * head_dim ||
-      v_token_stride < (int64_t)n_kv_heads * head_dim)
-    return HYDRA_ERR_INVALID_ARG;
-  if ((q_token_stride | k_token_stride | v_token_stride) & 7) return HYDRA_ERR_INVALID_ARG;
-  if (int rc = check_workspace(workspace, workspace_bytes, hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads))) return rc;
+  // every check of both halves runs before the first launch, so that an error never leaves half the work enqueued
+  bool done = false;
+  unsigned cus = 0;
+  if (int rc = validate_attn_call(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                                  n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, &done, &cus))
+    return rc;
+  if (done) return HYDRA_OK;
 
   if (int rc = hydra_attn_build_worklist(cu_seqlens, batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim, causal, workspace,
                                          workspace_bytes, stream))
@@ -301,21 +335,22 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
   const dim3 grid((unsigned)(tile_wgs + rows_wgs), 1, 1);
   const dim3 combine_grid((unsigned)n_kv_heads, (unsigned)batch);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t err;
   switch (head_dim) {
     case 64:
-      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), 0, s, args);
-      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<64>, combine_grid, dim3(256), 0, s, args);
+      err = launch(hydra::paged::attn_paged_kernel<64>, grid, dim3(256), s, args);
+      if (err == hipSuccess && splits > 1) err = launch(hydra::paged::attn_paged_combine_kernel<64>, combine_grid, dim3(256), s, args);
       break;
     case 80:
-      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<80>, grid, dim3(256), 0, s, args);
-      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<80>, combine_grid, dim3(256), 0, s, args);
+      err = launch(hydra::paged::attn_paged_kernel<80>, grid, dim3(256), s, args);
+      if (err == hipSuccess && splits > 1) err = launch(hydra::paged::attn_paged_combine_kernel<80>, combine_grid, dim3(256), s, args);
       break;
     default:
-      hipLaunchKernelGGL(hydra::paged::attn_paged_kernel<128>, grid, dim3(256), 0, s, args);
-      if (splits > 1) hipLaunchKernelGGL(hydra::paged::attn_paged_combine_kernel<128>, combine_grid, dim3(256), 0, s, args);
+      err = launch(hydra::paged::attn_paged_kernel<128>, grid, dim3(256), s, args);
+      if (err == hipSuccess && splits > 1) err = launch(hydra::paged::attn_paged_combine_kernel<128>, combine_grid, dim3(256), s, args);
       break;
   }
-  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+  return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 size_t hydra_attn_paged_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32_t head_dim, int32_t max_blocks_per_seq, int32_t block_size) {
@@ -351,8 +386,8 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
   int64_t blocks = (pieces + hydra::kKvWriteThreads - 1) / hydra::kKvWriteThreads;
   const int64_t max_blocks = 256 * 32;  // grid-stride beyond this
   if (blocks > max_blocks) blocks = max_blocks;
-  hipLaunchKernelGGL(hydra::kv_cache_write_kernel, dim3((unsigned)blocks), dim3(hydra::kKvWriteThreads), 0, static_cast<hipStream_t>(stream), args);
-  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+  const hipError_t err = launch(hydra::kv_cache_write_kernel, dim3((unsigned)blocks), dim3(hydra::kKvWriteThreads), static_cast<hipStream_t>(stream), args);
+  return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 namespace {
@@ -377,16 +412,17 @@ int launch_page_cache(bool gather, const void* packed, int64_t packed_row_stride
   const int64_t max_blocks = 256 * 32;  // grid-stride beyond this
   if (blocks > max_blocks) blocks = max_blocks;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t err;
   if (gather) {
     args.src = static_cast<const uint4*>(cache);
     args.dst = static_cast<uint4*>(const_cast<void*>(packed));
-    hipLaunchKernelGGL(hydra::page_cache_kernel<true>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), 0, s, args);
+    err = launch(hydra::page_cache_kernel<true>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), s, args);
   } else {
     args.src = static_cast<const uint4*>(packed);
     args.dst = static_cast<uint4*>(const_cast<void*>(cache));
-    hipLaunchKernelGGL(hydra::page_cache_kernel<false>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), 0, s, args);
+    err = launch(hydra::page_cache_kernel<false>, dim3((unsigned)blocks), dim3(hydra::kPageCacheThreads), s, args);
   }
-  return hipGetLastError() == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
+  return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
 }  // namespace

@@ -1,7 +1,7 @@
 // Paged image cache: rows of the vision encoder's output -> cache pages, and back.
 //
 // The paper keeps the encoder's image tokens in an image cache that is paged like the KV cache
-// (Section 5: "a paged management approach for image caching like kv cache"; image-cache block size
+// (Section 4.5; image-cache block size
 // 576 in Section 5.1), so that a request can migrate between instances and repeated images can be
 // reused.  Both directions are pure data movement (HBM-bound): one thread per 16-byte piece of a
 // row, 128-bit loads and stores, the lanes of a row consecutive on both sides.

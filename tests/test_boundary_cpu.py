@@ -78,6 +78,12 @@ def test_attn_argument_errors(lib):
     assert _attn(lib, ws=None) == WORKSPACE
     assert _attn(lib, ws_bytes=8) == WORKSPACE
     assert _attn(lib, ws=24) == WORKSPACE  # misaligned workspace
+    # K/V byte offsets inside one sequence beyond 31 bits: refused by the combined call before its first
+    # launch (a launch attempt would fail differently here: there is no device, and the addresses are fake)
+    big = hydra.hydra_attn_workspace_bytes(1, 1 << 20, 1 << 20, 2, 2, 64)
+    assert _attn(lib, total=1 << 20, max_len=1 << 20, ks=2048, ws_bytes=big) == UNSUPPORTED
+    assert _attn(lib, total=1 << 20, max_len=1 << 20, vs=1 << 20, ws_bytes=big) == UNSUPPORTED
+    assert lib.hydra_attn_varlen_fwd_prebuilt(16, 16, 16, 16, 128, 2048, 128, 16, 1, 1 << 20, 1 << 20, 2, 2, 64, 0, 0.125, 16, big, None) == UNSUPPORTED
     # empty batches succeed without touching any pointer
     assert _attn(lib, batch=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0
     assert _attn(lib, total=0, q=None, k=None, v=None, out=None, cu=None, ws=None) == 0

@@ -33,7 +33,7 @@ def _run_gpu(w, q, k, v, causal=None, scale=None, **kw):
     return out
 
 
-def _check(out, want, rows=None):
+def _check(out, want):
     got = _f64(out)
     assert np.isfinite(got).all()
     diff = np.abs(got - want)
@@ -125,7 +125,7 @@ def test_out_of_range_rows_untouched_and_deterministic():
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 80, 128])
 def test_large_scores_take_careful_path(d, causal):
     """Keys planted after the first key block whose scores lead the block-0 maximum by far more than
     the fast kernel's range (row sums beyond 2^40 times the reference term): it flags the affected work items and the careful kernel redoes them (if it
@@ -302,31 +302,17 @@ FULL = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode", "
 
 
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_configs_sampled(name):
-    """Benchmark-size workloads in the launch configuration the benchmark times: sampled output rows
-    against the oracle (row by row), plus whole-output properties (finite; convexity bound)."""
+def test_full_size_configs_whole_output(name):
+    """Benchmark-size workloads in the launch configuration the benchmark times (persistent workgroups, per-die
+    queues with stealing, ordered queue tails): EVERY output element against the C oracle."""
     w = si.WORKLOADS[name]()
     q, k, v = si.make_qkv(w)
     out = _run_gpu(w, q, k, v)
-    rng = np.random.default_rng(123)
-    rows = []
-    cu = w.cu_seqlens
-    for b in range(w.batch):  # first, last and tile-boundary tokens of every sequence, random heads
-        L = w.lengths[b]
-        for i in {0, L - 1, min(63, L - 1), min(64, L - 1), L // 2}:
-            rows.append((int(cu[b]) + i, int(rng.integers(w.n_q_heads))))
-    for _ in range(128):
-        rows.append((int(rng.integers(w.total_tokens)), int(rng.integers(w.n_q_heads))))
-    want = c_oracle.attn_rows(_f64(q), _f64(k), _f64(v), cu, w.causal, w.softmax_scale, rows)
-    got_all = out.cpu()
-    got = np.stack([_f64(got_all[t, h]) for t, h in rows])
-    diff = np.abs(got - want)
-    print(f"{name}: sampled rows {len(rows)}  max abs {diff.max():.3e}  mean abs {diff.mean():.3e}")
-    assert diff.max() <= MAX_ABS and diff.mean() <= MEAN_ABS
-    gf = got_all.float()
-    assert torch.isfinite(gf).all()
+    want = c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, w.causal, w.softmax_scale)
+    print(name, end=": ")
+    _check(out, want)
     # every output is a convex combination of V rows: bounded by the global V range
-    assert gf.abs().max() <= v.float().abs().max() * 1.01
+    assert out.float().abs().max() <= v.float().abs().max() * 1.01
 
 
 def _kv_case(w, strided=False, skip_fraction=0.0, spare=8):
