@@ -130,6 +130,31 @@ int hydra_attn_varlen_fwd_shared(const void* q, const void* k, const void* v, vo
                                  void* workspace, size_t workspace_bytes, int32_t workgroups_per_cu, void* stream);
 
 /*
+ * hydra_attn_varlen_fwd for callers that cannot allocate device memory or have none to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The work list,
+ * counters and flags live in an array of HYDRA_ATTN_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy until the process ends);
+ * the call allocates and frees nothing, and neither does anything it calls.
+ *
+ *   - Arguments, layouts, arithmetic and results (bit for bit) are those of hydra_attn_varlen_fwd
+ *     without the workspace pair.
+ *   - A batch whose hydra_attn_workspace_bytes(...) exceeds HYDRA_ATTN_STATIC_SCRATCH_BYTES is
+ *     refused with HYDRA_ERR_WORKSPACE before anything is launched (4 MiB holds, for example,
+ *     4096 sequences with 262 144 tokens at 32 query heads).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it.  Calls on one stream are ordered and safe; the array keeps
+ *     the previous call's contents and every call rewrites all of what it reads.
+ *   - The first call on a device looks the array's address up (a runtime query, not an allocation);
+ *     make that first call outside a graph capture.
+ */
+#define HYDRA_ATTN_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int hydra_attn_varlen_fwd_static(const void* q, const void* k, const void* v, void* out,
+                                 int64_t q_token_stride, int64_t k_token_stride, int64_t v_token_stride,
+                                 const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                 int32_t causal, float softmax_scale, void* stream);
+
+/*
  * Scatter of the prefill K/V of a packed batch into a paged KV cache (Section 5.1: KV-cache block
  * size 16; the per-request page tables of Section 4.3 are flattened by the caller into one slot per
  * token, slot = block_id * block_size + offset_in_block).

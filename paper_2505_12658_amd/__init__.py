@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     hydra_attn_varlen_fwd,
     hydra_attn_varlen_fwd_prebuilt,
     hydra_attn_varlen_fwd_shared,
+    hydra_attn_varlen_fwd_static,
     hydra_attn_workspace_bytes,
     hydra_kv_cache_write,
     hydra_page_cache_gather,

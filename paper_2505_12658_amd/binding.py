@@ -42,6 +42,8 @@ def load_library() -> ctypes.CDLL:
         lib.hydra_attn_varlen_fwd_prebuilt.argtypes = lib.hydra_attn_varlen_fwd.argtypes
         lib.hydra_attn_varlen_fwd_shared.restype = ctypes.c_int
         lib.hydra_attn_varlen_fwd_shared.argtypes = lib.hydra_attn_varlen_fwd.argtypes[:-1] + [i32, vp]
+        lib.hydra_attn_varlen_fwd_static.restype = ctypes.c_int
+        lib.hydra_attn_varlen_fwd_static.argtypes = lib.hydra_attn_varlen_fwd.argtypes[:-3] + [vp]
         lib.hydra_attn_build_worklist.restype = ctypes.c_int
         lib.hydra_attn_build_worklist.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         lib.hydra_kv_cache_write.restype = ctypes.c_int
@@ -110,6 +112,26 @@ def hydra_attn_varlen_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != HYDRA_OK:
         raise HydraError(rc, "hydra_attn_varlen_fwd")
+    return out
+
+
+def hydra_attn_varlen_fwd_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, causal: bool,
+                                 softmax_scale: float, out: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """hydra_attn_varlen_fwd with the work list in the library's own static device array: nothing is allocated,
+    here or in the library, so `out` is the caller's."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _check_token_major(t, n)
+    if cu_seqlens.dtype != torch.int32 or not cu_seqlens.is_cuda or not cu_seqlens.is_contiguous():
+        raise TypeError("cu_seqlens must be a contiguous CUDA int32 tensor")
+    N, Hq, d = q.shape
+    if not out.is_contiguous() or out.shape != (N, Hq, d) or out.dtype != torch.bfloat16:
+        raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+    rc = lib.hydra_attn_varlen_fwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), q.stride(0), k.stride(0), v.stride(0),
+                                          cu_seqlens.data_ptr(), cu_seqlens.numel() - 1, N, int(max_seqlen), Hq, k.shape[1], d,
+                                          int(bool(causal)), float(softmax_scale), _stream_handle(stream))
+    if rc != HYDRA_OK:
+        raise HydraError(rc, "hydra_attn_varlen_fwd_static")
     return out
 
 

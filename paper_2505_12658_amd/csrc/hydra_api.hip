@@ -4,6 +4,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <tuple>
 
 #include "../../include/hydra_attn.h"
@@ -273,6 +274,55 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
   return hydra_attn_varlen_fwd_prebuilt(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens,
                                         max_seqlen, n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, workspace, workspace_bytes,
                                         stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Work-list memory of hydra_attn_varlen_fwd_static: one array per device, living in the code
+// object's data segment, so that a caller that may not allocate needs no workspace of its own.
+constexpr size_t kStaticScratchBytes = HYDRA_ATTN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle for the runtime, so the address is asked for once per device (with that device current)
+// and kept; every use below goes through this pointer.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HYDRA_ERR_LAUNCH;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HYDRA_ERR_LAUNCH;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // (two first callers get the same address)
+  }
+  *ptr = p;
+  return HYDRA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hydra_attn_varlen_fwd_static(const void* q, const void* k, const void* v, void* out, int64_t q_token_stride, int64_t k_token_stride,
+                                 int64_t v_token_stride, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens,
+                                 int32_t max_seqlen, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t causal,
+                                 float softmax_scale, void* stream) {
+  // sizes first: the work list of this call has to fit the static array
+  if (int rc = check_attn_sizes(batch, total_tokens, max_seqlen, n_q_heads, n_kv_heads, head_dim)) return rc;
+  if (batch == 0 || total_tokens == 0)  // nothing to launch; the remaining argument checks are the plain call's
+    return hydra_attn_varlen_fwd(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                                 n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, nullptr, 0, stream);
+  if (hydra::workspace_layout(batch, total_tokens, n_q_heads, n_kv_heads).total > kStaticScratchBytes) return HYDRA_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (int rc = static_scratch(&ws)) return rc;
+  // The prepass rewrites every word of the work list, the counters and the flags that the attention
+  // kernels read, so whatever the previous call left in the array does not matter.
+  return hydra_attn_varlen_fwd(q, k, v, out, q_token_stride, k_token_stride, v_token_stride, cu_seqlens, batch, total_tokens, max_seqlen,
+                               n_q_heads, n_kv_heads, head_dim, causal, softmax_scale, ws, kStaticScratchBytes, stream);
 }
 
 int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const void* k_cache, const void* v_cache,

@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_paged_workspace_bytes", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_varlen_fwd_shared", "hydra_attn_workspace_bytes",
+    assert names == ["hydra_attn_build_worklist", "hydra_attn_paged_fwd", "hydra_attn_paged_workspace_bytes", "hydra_attn_varlen_fwd", "hydra_attn_varlen_fwd_prebuilt", "hydra_attn_varlen_fwd_shared", "hydra_attn_varlen_fwd_static", "hydra_attn_workspace_bytes",
                      "hydra_kv_cache_write", "hydra_page_cache_gather", "hydra_page_cache_write", "hydra_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -98,6 +98,21 @@ def test_shared_attn_argument_errors(lib):
     assert call(1, q=None) == 1
     assert call(1, d=96) == 2
     assert call(2, ws_bytes=8) == 3
+
+
+def test_static_scratch_attn_argument_errors(lib):
+    """The allocation-free variant: same host-side checks, and a batch whose work list does not fit its static
+    array is refused before anything is launched (fake addresses throughout)."""
+    def call(q=16, batch=1, total=8, max_len=8, hq=2, hkv=2, d=64, scale=0.125):
+        return lib.hydra_attn_varlen_fwd_static(q, 16, 16, 16, hq * d, hkv * d, hkv * d, 16, batch, total, max_len, hq, hkv, d, 1, scale, None)
+    limit = 4 << 20
+    assert hydra.hydra_attn_workspace_bytes(4096, 262144, 4096, 32, 8, 128) <= limit < hydra.hydra_attn_workspace_bytes(4096, 1 << 20, 4096, 32, 8, 128)
+    assert call(batch=4096, total=1 << 20, max_len=4096, hq=32, hkv=8, d=128) == 3
+    assert call(d=96) == 2
+    assert call(hq=3) == 1
+    assert call(batch=-1) == 1
+    assert call(batch=0, q=None) == 0
+    assert call(batch=0, q=None, scale=-1.0) == 1
 
 
 def _kvw(lib, k=16, v=16, ks=128, vs=128, kc=16, vc=16, slots=16, total=4, hkv=2, d=64, bs=16, nb=4, stream=None):
