@@ -285,12 +285,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t qreg_t;
 __device__ __forceinline__ void mfma_pv(f32x16_t& O, const bf16x8_t& vf, const bf16x8_t& pf) {
   O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, O, 0, 0, 0);
 }
-// S = A(kf) * B(q) + init, then S += A(kf) * B(q)
+// S = A(kf) * B(q), then S += A(kf) * B(q)
 __device__ __forceinline__ void mfma_qk_zero(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(kf), "v"(q));
-}
-__device__ __forceinline__ void mfma_qk_init(f32x16_t& S, const f32x16_t& init, const bf16x8_t& kf, const qreg_t& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(kf), "v"(q), "v"(init));
 }
 __device__ __forceinline__ void mfma_qk_acc(f32x16_t& S, const bf16x8_t& kf, const qreg_t& q) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(kf), "v"(q));
@@ -335,10 +332,17 @@ constexpr int kKeyBlock = 32;         // keys per pipeline step
 template <int N>
 using NextRB = std::integral_constant<int, N>;  // key block the following step reads in the same tiles (-1: none)
 
+// LDS fragments are requested this many work units (one K or V^T fragment and the matrix instructions it feeds)
+// ahead of their use.  Each unit of distance keeps one more K and one more V^T fragment (8 registers) in flight.
+// (A distance of three was measured at head_dim 80 and 128, which have the registers: no faster.)
+template <int D>
+constexpr int kFragsAhead = 2;
+
 #if defined(__HIP_DEVICE_COMPILE__)
-// LDS fragments of the first two QK units (k0, k1) and the first two PV units (v0, v1) of a pipeline step.
+// LDS fragments of the first PF QK units and the first PF PV units of a pipeline step.
+template <int PF>
 struct StepFrags {
-  bf16x8_t k0, k1, v0, v1;
+  bf16x8_t k[PF], v[PF];
 };
 #endif
 constexpr float kMaxRowSum = 1.0995116e12f;  // 2^40: largest row sum (relative to the reference) the fast kernel accepts
@@ -356,6 +360,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   constexpr int ROWB = G::kRowBytes;
   constexpr int NQ = KS;      // QK work units per key block: step s = one K fragment read + 2 MFMAs (qs = 0, 1)
   constexpr int NP = 2 * CC;  // PV work units per key block: (s2, cc) = one V^T fragment + 2 MFMAs
+  constexpr int PF = kFragsAhead<D>;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
   // LDS: K ring then V ring; tile t of either lives in ring slot t % kRing.
   constexpr int R = G::kRing, PD = G::kPrefetch;
@@ -495,12 +500,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   k_loader.issue_next(k_ring);
 
   if (!q_ahead) issue_q_loads(seq_start, seq_len, q0, head, lane);
-  // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7,
-  // already scaled (see below).
+  // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7, as
+  // they come from memory.  The softmax scale is applied to the scores in fp32 (see softmax_half).
   const float c = a.scale_log2;
   qreg_t qf[QS][KS];
   int q_lim[QS];  // largest visible key index for this lane's query of sub-tile qs
-  bf16x8_t q_raw[QS][KS];
   wait_all_loads();  // Q (and this wave's part of K(0)) has landed
 #pragma unroll
   for (int qs = 0; qs < QS; ++qs) {
@@ -509,25 +513,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     q_lim[qs] = CAUSAL ? row : seq_len - 1;
 #pragma unroll
     for (int s = 0; s < KS; ++s)
-      q_raw[qs][s] = *reinterpret_cast<const bf16x8_t*>(HYDRA_LDS_BYTE(q_stage + (32 * qs + m) * ROWB + k_swizzle<D>(32 * qs + m, KS * hf + s) * 16));
+      qf[qs][s] = *reinterpret_cast<const qreg_t*>(HYDRA_LDS_BYTE(q_stage + (32 * qs + m) * ROWB + k_swizzle<D>(32 * qs + m, KS * hf + s) * 16));
   }
-
-  // Q' = bf16(Q * scale * log2 e): the scores come out of the matrix unit in log2 units, and with the
-  // accumulator started at -reference the softmax needs one v_exp per score.
-#pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      bf16x8_t scaled;
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        f32x2_t f = {(float)q_raw[qs][s][e] * c, (float)q_raw[qs][s][e + 1] * c};
-        const bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
-        scaled[e] = b[0];
-        scaled[e + 1] = b[1];
-      }
-      qf[qs][s] = __builtin_bit_cast(qreg_t, scaled);
-    }
 
   // LDS read addresses: lane part + ring slot of the iteration's K tile / V tile; the key block
   // inside the tile and the step are immediates.  Advanced once per iteration.
@@ -569,16 +556,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[qs][cc][r] = 0.f;
-  // Softmax reference: the row maximum over key block 0, kept for the whole row.  Every later
-  // score accumulator starts at -reference, so the matrix unit hands back (score - reference) in
-  // log2 units and the exponential needs no further arithmetic; O never has to be rescaled
-  // inside the loop.  That is exact as long as the exponentials stay far from the end of the fp32
+  // Softmax reference: the row maximum over key block 0, kept for the whole row, so O never has to be
+  // rescaled inside the loop.  The matrix unit returns raw scores <q, k>; scale and reference go in with
+  // one fused multiply-add per score, p = exp2(score * c - reference * c), c = softmax_scale * log2 e.
+  // That is exact as long as the exponentials stay far from the end of the fp32
   // range: a wave whose row sums (which bound every single exponential) exceed kMaxRowSum, or are
   // not finite, flags its work item, and the flagged items are recomputed afterwards by the careful
   // kernel, which rescales at every tile.  (bf16 activations lead the first block's maximum by a few
   // powers of two at most.  Below the limit the unnormalised output is bounded by 2^40 times the sum
   // of |V| over the keys, so it cannot overflow for |V| up to 10^20.)
-  f32x16_t neg_ref[QS];  // -reference, broadcast over the 16 registers of a block
+  float nref[QS];        // -reference * c of this lane's query row
   float row_sum[QS];     // this lane's half of the row sum
 #pragma unroll
   for (int qs = 0; qs < QS; ++qs) row_sum[qs] = 0.f;
@@ -613,22 +600,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int min_lim = CAUSAL ? q0 : seq_len - 1;
   auto needs_mask = [&](int j) { return j * kKeyBlock + kKeyBlock - 1 > min_lim; };
 
-  // softmax of one pair of elements (pair 0..15: sub-tile pair / 8, registers 2*(pair%8), +1) of a
-  // key block whose S already holds (score - reference): exponentials, row sum, rounding to bf16.
+  // Softmax of a key block whose S holds the raw scores, in 16 * QS halves of an element pair (pair = half / 2:
+  // sub-tile pair / 8, registers 2 * (pair % 8), +1): scale and reference, exponentials, row sum, rounding to
+  // bf16.  A half is one exponential (a quarter-rate instruction) and two or three full-rate ones, about as long
+  // as one matrix instruction takes, so that a wave alone on its SIMD can put one behind every matrix
+  // instruction and keep the matrix pipe fed; whole pairs behind every other instruction left it idle a third
+  // of the time.  The first half leaves its results in the two S registers.
   // (The sum is two plain adds on purpose: the 2-element dot-product instruction would halve them,
   // but it runs in the matrix pipe and stalls behind the matrix instructions it is meant to hide in.)
-  auto softmax_pair = [&](int pair, const f32x16_t(&Sc)[QS], bf16x8_t(&Pc)[QS][2], float(&psum)[QS]) __attribute__((always_inline)) {
-    const int qs = pair / 8, r = 2 * (pair % 8);
-    f32x2_t pr = {fast_exp2(Sc[qs][r]), fast_exp2(Sc[qs][r + 1])};
-    if constexpr (!G::kSumsFromMatrixUnit) {
-      psum[qs] += pr[0];
-      psum[qs] += pr[1];
+  auto softmax_half = [&](int half, f32x16_t(&Sc)[QS], bf16x8_t(&Pc)[QS][2], float(&psum)[QS]) __attribute__((always_inline)) {
+    const int pair = half / 2, qs = pair / 8, r = 2 * (pair % 8);
+    if (half % 2 == 0) {
+      float e0 = fast_exp2(__builtin_fmaf(Sc[qs][r], c, nref[qs]));
+      float x1 = __builtin_fmaf(Sc[qs][r + 1], c, nref[qs]);
+      asm volatile("" : "+v"(e0), "+v"(x1));  // keeps this half's work where it is written
+      Sc[qs][r] = e0;
+      Sc[qs][r + 1] = x1;
+    } else {
+      float x1 = Sc[qs][r + 1];
+      asm volatile("" : "+v"(x1));  // the second exponential stays behind the matrix instruction it is meant to follow
+      f32x2_t pr = {Sc[qs][r], fast_exp2(x1)};
+      if constexpr (!G::kSumsFromMatrixUnit) {
+        psum[qs] += pr[0];
+        psum[qs] += pr[1];
+      }
+      uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
+      asm volatile("" : "+v"(packed), "+v"(psum[qs]));
+      const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
+      Pc[qs][r / 8][r % 8] = pk[0];
+      Pc[qs][r / 8][r % 8 + 1] = pk[1];
     }
-    uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
-    asm volatile("" : "+v"(packed), "+v"(psum[qs]));  // keeps this pair's work where it is written
-    const bf16x2_t pk = __builtin_bit_cast(bf16x2_t, packed);
-    Pc[qs][r / 8][r % 8] = pk[0];
-    Pc[qs][r / 8][r % 8 + 1] = pk[1];
   };
 
   // One pipeline step for key block j >= 1 of this wave.  KRB / VRB: key block of K(j+1) and of
@@ -638,25 +639,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // One matrix instruction, then the share of vector work that fits in its shadow, and so on:
   // the wave issues in order, so this is what lets the two pipes run side by side.
   constexpr int NM = QS * (NQ + NP);  // matrix instructions per step
-  constexpr int NV = 8 * QS;          // vector work pieces per step: 8 element pairs per sub-tile
+  constexpr int NV = 16 * QS;         // vector work pieces per step: the halves of 8 element pairs per sub-tile
   // qk_tag: false for a wave's last step, which has no S(j+1) to compute.
-  // The LDS fragments of a step's first two QK units and first two PV units are fetched ahead of the
-  // step (the LDS answers after roughly two matrix instructions; fetched at the top of the step that
+  // The LDS fragments of a step's first PF QK units and first PF PV units are fetched ahead of the
+  // step (the LDS answers after several matrix instructions; fetched at the top of the step that
   // latency would be exposed once per step): `fr` holds them on entry.  next_tag >= 0: the step that
   // follows reads key block next_tag of the SAME tiles, and this step's last units fetch its first
   // fragments into `fr` (next_qk_tag: whether it has QK units).  next_tag < 0: nothing is fetched ahead
   // (the next tiles are only complete after the iteration's barrier; the caller fetches them then).
   auto block_step = [&](auto rb_tag, auto qk_tag, auto next_tag, auto next_qk_tag, int j, f32x16_t(&Sc)[QS], f32x16_t(&Sn)[QS],
-                        const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2], StepFrags& fr, int koff, int voff) __attribute__((always_inline)) {
+                        const bf16x8_t(&Pp)[QS][2], bf16x8_t(&Pc)[QS][2], StepFrags<PF>& fr, int koff, int voff) __attribute__((always_inline)) {
     constexpr int RB = decltype(rb_tag)::value;  // step 2t-1: K(2t), V(2t-2) -> 0; step 2t: K(2t+1), V(2t-1) -> 1
     constexpr bool QK = decltype(qk_tag)::value;
     constexpr int NEXT_RB = decltype(next_tag)::value;
     constexpr bool NEXT_QK = decltype(next_qk_tag)::value;
     constexpr int NMS = QK ? NM : QS * NP;       // matrix instructions of this step
     if (needs_mask(j)) apply_mask(j, Sc);
-    // vector work piece i of this step: one softmax pair (its exponentials go straight onto the row sum)
-    auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_pair(i, Sc, Pc, row_sum); };
-    bf16x8_t kf_cur = fr.k0, kf_nxt = fr.k1, vf_cur = fr.v0, vf_nxt = fr.v1, kf_nn, vf_nn;
+    // vector work piece i of this step: half a softmax pair
+    auto valu_piece = [&](int i) __attribute__((always_inline)) { softmax_half(i, Sc, Pc, row_sum); };
+    // kq[i] / vq[i]: fragment of the QK / PV unit i places ahead of the one that runs next
+    bf16x8_t kq[PF], vq[PF], k_new, v_new;
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+      kq[i] = fr.k[i];
+      vq[i] = fr.v[i];
+    }
     int ms = 0;  // matrix-instruction index inside the step
     auto shadow = [&](int ms_done) __attribute__((always_inline)) {
       // vector pieces [ms*NV/NMS, (ms+1)*NV/NMS) run behind matrix instruction ms
@@ -667,46 +674,53 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     // Order: QK unit 0, then alternately QK unit u and PV unit u - 1; the step ends with (at least)
     // two PV units, whose matrix instructions cover the wait states of the last QK result.
     static_assert(NP >= NQ && NP >= 2, "the step must end with two PV units");
+    static_assert(NQ >= PF && NP >= PF, "a step's last units fetch the next step's first fragments");
 #pragma unroll
     for (int u = 0; u <= NP; ++u) {
       if (QK && u < NQ) {
-        if (u + 2 < NQ) kf_nn = load_k_frag(RB, u + 2, koff);
-        else if (NEXT_RB >= 0 && NEXT_QK && u + 2 - NQ < NQ) kf_nn = load_k_frag(NEXT_RB, u + 2 - NQ, koff);
+        const bool k_more = u + PF < NQ || (NEXT_RB >= 0 && NEXT_QK);
+        if (u + PF < NQ) k_new = load_k_frag(RB, u + PF, koff);
+        else if (NEXT_RB >= 0 && NEXT_QK) k_new = load_k_frag(NEXT_RB, u + PF - NQ, koff);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          if (u == 0) mfma_qk_init(Sn[qs], neg_ref[qs], kf_cur, qf[qs][u]); else mfma_qk_acc(Sn[qs], kf_cur, qf[qs][u]);
+          if (u == 0) mfma_qk_zero(Sn[qs], kq[0], qf[qs][u]); else mfma_qk_acc(Sn[qs], kq[0], qf[qs][u]);
           shadow(ms++);
         }
-        kf_cur = kf_nxt;
-        kf_nxt = kf_nn;
+#pragma unroll
+        for (int i = 0; i + 1 < PF; ++i) kq[i] = kq[i + 1];
+        if (k_more) kq[PF - 1] = k_new;
       }
       if (u >= 1) {
         const int pu = u - 1;
-        if (pu + 2 < NP) vf_nn = load_v_frag(RB, pu + 2, voff);
-        else if (NEXT_RB >= 0) vf_nn = load_v_frag(NEXT_RB, pu + 2 - NP, voff);
+        const bool v_more = pu + PF < NP || NEXT_RB >= 0;
+        if (pu + PF < NP) v_new = load_v_frag(RB, pu + PF, voff);
+        else if (NEXT_RB >= 0) v_new = load_v_frag(NEXT_RB, pu + PF - NP, voff);
         const int cc = pu % CC, s2 = pu / CC;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          mfma_pv(o_acc[qs][cc], vf_cur, Pp[qs][s2]);
+          mfma_pv(o_acc[qs][cc], vq[0], Pp[qs][s2]);
           shadow(ms++);
         }
-        vf_cur = vf_nxt;
-        vf_nxt = vf_nn;
+#pragma unroll
+        for (int i = 0; i + 1 < PF; ++i) vq[i] = vq[i + 1];
+        if (v_more) vq[PF - 1] = v_new;
       }
     }
     if constexpr (NEXT_RB >= 0) {
-      fr.k0 = kf_cur;
-      fr.k1 = kf_nxt;
-      fr.v0 = vf_cur;
-      fr.v1 = vf_nxt;
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        fr.k[i] = kq[i];
+        fr.v[i] = vq[i];
+      }
     }
   };
   // first fragments of a step that reads key block rb of the tiles the address registers point at
-  auto fetch_step_frags = [&](int rb, bool with_qk, StepFrags& fr, int koff, int voff) __attribute__((always_inline)) {
-    fr.v0 = load_v_frag(rb, 0, voff);
-    if (with_qk) fr.k0 = load_k_frag(rb, 0, koff);
-    fr.v1 = load_v_frag(rb, 1, voff);
-    if (with_qk) fr.k1 = load_k_frag(rb, 1, koff);
+  auto fetch_step_frags = [&](int rb, bool with_qk, StepFrags<PF>& fr, int koff, int voff) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+      fr.v[i] = load_v_frag(rb, i, voff);
+      if (with_qk) fr.k[i] = load_k_frag(rb, i, koff);
+    }
   };
 
   // PV only (after this wave's last softmax): O += V^T P for key block rb of the V tile in reach
@@ -739,8 +753,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
   }
 
-  // iteration 0 (not overlapped): S(0) = K(0) Q'^T, reference = row maximum of block 0, softmax of
-  // block 0, S(1) = K(1) Q'^T - reference
+  // iteration 0: S(0) = K(0) Q^T alone, then S(1) = K(1) Q^T with the vector work of block 0 in its
+  // shadow (reference = row maximum of block 0, softmax of block 0)
   if (NB > 0) {
     // (the K fragments of both blocks are requested ahead of the matrix instructions that use them,
     // with scheduling fences in between: see pv_only)
@@ -759,28 +773,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 #pragma unroll
     for (int s = 0; s < NQ; ++s) kf1[s] = load_k_frag(1, s, 0);
     HYDRA_SCHED_FENCE();
-    s_results_to_valu(s_a);
-    if (needs_mask(0)) apply_mask(0, s_a);
+    // (S(1) is computed even when NB == 1: harmless, never read.)  Its first two matrix instructions cover
+    // the wait states of S(0); the vector work follows behind the others.
+    static_assert(NQ * QS >= 4, "two matrix instructions ahead of the first read of S(0), at least two to hide the vector work behind");
+    constexpr int kLead = 2;
+    int mi = 0;
+    auto block0_valu = [&](int piece, int pieces) __attribute__((always_inline)) {
+      // piece 0: mask and row maximum; the 16 * QS softmax halves are spread over the others
+      if (piece == 0) {
+        if (needs_mask(0)) apply_mask(0, s_a);
 #pragma unroll
-    for (int qs = 0; qs < QS; ++qs) {
-      float t = fmaxf(s_a[qs][0], s_a[qs][1]);
+        for (int qs = 0; qs < QS; ++qs) {
+          float t = fmaxf(s_a[qs][0], s_a[qs][1]);
 #pragma unroll
-      for (int r = 2; r < 16; ++r) t = fmaxf(t, s_a[qs][r]);
-      t = max_with_other_half(t);
+          for (int r = 2; r < 16; ++r) t = fmaxf(t, s_a[qs][r]);
+          t = max_with_other_half(t);
+          nref[qs] = -t * c;
+        }
+      } else {
+        const int n = 16 * QS, per = (n + pieces - 2) / (pieces - 1);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        neg_ref[qs][r] = -t;
-        s_a[qs][r] -= t;
+        for (int half = (piece - 1) * per; half < piece * per && half < n; ++half) softmax_half(half, s_a, p_a, row_sum);
       }
-    }
+      HYDRA_SCHED_FENCE();
+    };
+    constexpr int kPieces = NQ * QS - kLead;
 #pragma unroll
-    for (int pair = 0; pair < 8 * QS; ++pair) softmax_pair(pair, s_a, p_a, row_sum);
-    HYDRA_SCHED_FENCE();
-#pragma unroll
-    for (int s = 0; s < NQ; ++s) {  // (computed even when NB == 1: harmless, never read)
+    for (int s = 0; s < NQ; ++s) {
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs) {
-        if (s == 0) mfma_qk_init(s_b[qs], neg_ref[qs], kf1[s], qf[qs][s]); else mfma_qk_acc(s_b[qs], kf1[s], qf[qs][s]);
+        if (s == 0) mfma_qk_zero(s_b[qs], kf1[s], qf[qs][s]); else mfma_qk_acc(s_b[qs], kf1[s], qf[qs][s]);
+        HYDRA_SCHED_FENCE();
+        if (mi >= kLead) block0_valu(mi - kLead, kPieces);
+        ++mi;
       }
     }
     s_results_to_valu(s_b);
@@ -826,7 +851,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const bool odd_steps = ((NB - 1) & 1) != 0;
   const int F_loop = odd_steps ? F : (F > 0 ? F - 1 : 0);
   int t = 1;
-  StepFrags fr;
+  StepFrags<PF> fr;
   // Inside its pipeline steps a wave goes ahead of the SIMD's other wave when that one is between items
   // (Q scaling, epilogue: long runs of vector instructions that would otherwise take every other issue slot).
   __builtin_amdgcn_s_setprio(1);

@@ -166,6 +166,37 @@ def test_large_scores_take_careful_path(d, causal):
     assert torch.equal(again.view(torch.int16), out.view(torch.int16))
 
 
+@pytest.mark.parametrize("amp", [2.0, 2.5, 3.0])
+@pytest.mark.parametrize("d", [64, 80, 128])
+def test_large_activations_stay_accurate_on_fast_path(d, amp):
+    """Q and K at 2x, 2.5x and 3x the unit amplitude (scores of standard deviation 4 to 9, peaked softmax): the scale
+    is applied to the fp32 scores, not folded into a re-rounded Q, so the error does not grow with the score.  At 2x
+    and 2.5x every row stays on the fast path: the kernel hands a work item to the careful one only when a row sum,
+    taken relative to the maximum of the row's first key block, goes beyond 2^40 (computed here from the fp64
+    scores); at 3x some rows come close to that limit and either kernel may serve."""
+    causal = d != 80
+    w = si.custom([300, 577, 64, 33], 4, 2, d, causal, seed=int(amp * 100) + d)
+    q, k, v = si.make_qkv(w)
+    q, k = (q.float() * amp).bfloat16(), (k.float() * amp).bfloat16()
+    # (a peaked softmax returns single V values; at unit amplitude some lie in [4, 8), where rounding the OUTPUT to
+    # bf16 alone costs up to 1.6e-2.  Halving V keeps that term at 7.8e-3, so that the bound tests the scores.)
+    v = (v.float() * 0.5).bfloat16()
+    qf, kf = _f64(q), _f64(k)
+    worst = 0.0  # largest row sum relative to the reference term (exponent of 2)
+    for b in range(w.batch):
+        s0, s1 = int(w.cu_seqlens[b]), int(w.cu_seqlens[b + 1])
+        for h in range(4):
+            z = w.softmax_scale * qf[s0:s1, h] @ kf[s0:s1, h // 2].T
+            if causal:
+                z = np.where(np.tril(np.ones_like(z, dtype=bool)), z, -np.inf)
+            ref = z[:, :32].max(axis=1, keepdims=True)
+            worst = max(worst, float(np.log2(np.exp(z - ref).sum(axis=1)).max()))
+    print(f"largest row sum 2^{worst:.1f}")
+    assert amp > 2.5 or worst < 38
+    out = _run_gpu(w, q, k, v)
+    _check(out, c_oracle.attn_varlen(qf, kf, _f64(v), w.cu_seqlens, causal, w.softmax_scale))
+
+
 @pytest.mark.parametrize("d,hq,hkv,causal", [(64, 4, 2, False), (80, 2, 2, False), (128, 7, 1, True)])
 def test_shared_variant_matches_plain_call(d, hq, hkv, causal):
     """The variant for two-stream callers (fewer persistent workgroups per compute unit) against the
