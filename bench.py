@@ -27,10 +27,25 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA, 256 CUs x 4096 FLOP/clk x 2
 PEAK_HBM_GBS = 8000.0
 CALIBRATION_COPY_BYTES = 1 << 30
 HEADLINE = "qwen2vl_7b_prefill"
-# HBM bytes per attention-kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes, scaled by the
-# calibration copy (factors 2.000 and 1.000): profiles/attn_fwd_qwen2vl_7b_prefill.md
-MEASURED_TRAFFIC_BYTES = {"qwen2vl_7b_prefill": 281.0e6 + 220.0e6}
 OTHERS = ["clip_vit_l14_336_encode", "llava15_7b_prefill", "qwen2vl_vit_encode"]
+
+
+def profile_figures(workload: str):
+    """Counter figures of the attention kernel on one workload, from the tracked rocprofv3 summary
+    profiles/attn_fwd_<workload>.md: its `figures:` line is a JSON object written together with the tables
+    (HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE passes scaled by the calibration copy, share of
+    cycles with the matrix pipe busy, kernel duration under the trace, the commit the profile was taken at).
+    Counters cannot be read inside a timed run, so the bench line carries them from there, with their source."""
+    path = os.path.join(ROOT, "profiles", f"attn_fwd_{workload}.md")
+    try:
+        for line in open(path):
+            if line.startswith("figures: "):
+                fig = json.loads(line[len("figures: "):])
+                fig["source"] = os.path.relpath(path, ROOT)
+                return fig
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 class DeviceBatch:
@@ -310,33 +325,47 @@ def paged_attention(dev, n_sets: int, steps: int):
     return report
 
 
-def image_cache(dev, steps: int):
+def image_cache(dev, steps: int, n_sets: int = 3):
     """Paged image cache (hydra_page_cache_write / hydra_page_cache_gather): encoder output rows into cache pages
-    and back.  HIP events around every launch; bytes = each row read once and written once + its slot."""
+    and back.  HIP events around every launch; bytes = each row read once and written once + its slot.  `frac` is
+    the cold figure: the launches rotate over `n_sets` separate sets of buffers (rows, cache, output), together
+    larger than the 256 MB last-level cache; `warm` repeats every launch on one set, which it partly or wholly
+    finds in that cache."""
     import paper_2505_12658_amd as hydra
 
     report = []
     for b in (si.llava15_image_cache(), si.qwen2vl_image_cache()):
-        rows = si.make_image_rows(b).to(dev)
+        host_rows = si.make_image_rows(b)
         slots, pages = si.make_slot_mapping(b.tokens, b.page_rows, spare_blocks=2, seed=b.seed)
         slots = torch.from_numpy(slots).to(dev)
-        cache = torch.zeros((pages, b.page_rows, b.hidden), dtype=torch.bfloat16, device=dev)
-        out = torch.empty_like(rows)
+        sets = [(host_rows.to(dev), torch.zeros((pages, b.page_rows, b.hidden), dtype=torch.bfloat16, device=dev)) for _ in range(n_sets)]
+        sets = [(rows, cache, torch.empty_like(rows)) for rows, cache in sets]
         entry = {"workload": b.name, "rows": b.n_rows, "row_elems": b.hidden, "page_rows": b.page_rows, "bytes": b.bytes_moved(), "bound": "hbm",
-                 "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-        for name, fn in (("write", lambda: hydra.hydra_page_cache_write(rows, cache, slots)),
-                         ("gather", lambda: hydra.hydra_page_cache_gather(cache, slots, out))):
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-            settle(lambda i: fn())
-            for e0, e1 in evs:
-                e0.record()
-                fn()
-                e1.record()
-            torch.cuda.synchronize()
-            avg = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e-3
-            entry[name] = {"avg_kernel_us": avg * 1e6, "achieved": b.bytes_moved() / avg * 1e-9, "frac": b.bytes_moved() / avg * 1e-9 / PEAK_HBM_GBS}
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "buffer_sets": n_sets}
+
+        def write(i):
+            rows, cache, _ = sets[i % n_sets]
+            hydra.hydra_page_cache_write(rows, cache, slots)
+
+        def gather(i):
+            _, cache, out = sets[i % n_sets]
+            hydra.hydra_page_cache_gather(cache, slots, out)
+
+        for name, fn in (("write", write), ("gather", gather)):
+            figures = {}
+            for label, pick in (("cold", lambda i: i), ("warm", lambda i: 0)):
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+                settle(lambda i: fn(pick(i)))
+                for i, (e0, e1) in enumerate(evs):
+                    e0.record()
+                    fn(pick(i))
+                    e1.record()
+                torch.cuda.synchronize()
+                avg = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e-3
+                figures[label] = {"avg_kernel_us": avg * 1e6, "achieved": b.bytes_moved() / avg * 1e-9, "frac": b.bytes_moved() / avg * 1e-9 / PEAK_HBM_GBS}
+            entry[name] = dict(figures["cold"], warm=figures["warm"])
         report.append(entry)
-        del rows, cache, out
+        del sets
         torch.cuda.empty_cache()
     return report
 
@@ -370,8 +399,9 @@ def main():
     ap.add_argument("--kv-write-side-stream", action="store_true",
                     help="`value` from the step with the KV scatter on a second stream behind the attention launch (measured equal to one stream)")
     ap.add_argument("--dual-stream", action="store_true",
-                    help="also measure an encode workload and the prefill workload launched together on two streams "
-                         "against the same two run one after the other (the paper's vision || language streams)")
+                    help="the two-stream measurements (an encode workload beside the prefill workload, and beside decode steps, "
+                         "launched together on two streams against the same launches one after the other: the paper's vision || "
+                         "language streams) at full length; the default run includes a short form of them")
     ap.add_argument("--paged-only", action="store_true", help="only the paged-attention measurements (for profiling that kernel)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 1 GiB (fp32 x + 0 -> y): the known-size kernel that "
@@ -398,6 +428,7 @@ def main():
     attn_t, kvw_t = time_kernels(batch, args.steps)
     hot_t, _ = time_kernels(batch, max(20, args.steps // 2), hot_cache=True)
     flops = w.attention_flops()
+    fig = profile_figures(w.name)
     attn_avg = float(attn_t.mean())
     achieved = flops / attn_avg * 1e-12
 
@@ -426,7 +457,10 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "traffic": fig["traffic_bytes"] if fig else None,
+            "traffic_over_algorithmic": fig["traffic_bytes"] / w.attention_min_bytes() if fig else None,
+            "mfma_busy": fig["mfma_busy"] if fig else None,
+            "counters_from": {k: fig[k] for k in ("source", "commit", "kernel_avg_us_under_trace")} if fig else None,
             "avg_kernel_us": attn_avg * 1e6,
             "median_kernel_us": float(np.median(attn_t)) * 1e6,
             "min_kernel_us": float(attn_t.min()) * 1e6,
@@ -468,6 +502,12 @@ def main():
                      "frac_hbm_peak": ow.attention_min_bytes() / float(at.mean()) * 1e-9 / PEAK_HBM_GBS}
             if kt is not None:
                 entry["kv_write_gbs"] = ow.kv_write_bytes() / float(kt.mean()) * 1e-9
+            ofig = profile_figures(name)
+            entry["algorithmic_bytes"] = ow.attention_min_bytes()
+            entry["traffic"] = ofig["traffic_bytes"] if ofig else None
+            entry["traffic_over_algorithmic"] = ofig["traffic_bytes"] / ow.attention_min_bytes() if ofig else None
+            entry["mfma_busy"] = ofig["mfma_busy"] if ofig else None
+            entry["counters_from"] = {k: ofig[k] for k in ("source", "commit", "kernel_avg_us_under_trace")} if ofig else None
             others.append(entry)
             del ob
             torch.cuda.empty_cache()
@@ -476,8 +516,9 @@ def main():
     if not args.no_others:
         result["paged_attention"] = paged_attention(dev, args.sets, max(20, args.steps // 4))
         result["image_cache"] = image_cache(dev, max(20, args.steps // 4))
-    if args.dual_stream:
-        result["dual_stream"] = dual_stream(dev, args.sets, max(20, args.steps // 4))
+    if args.dual_stream or not args.no_others:
+        # (short form in the default run; --dual-stream takes as many steps as the other secondary measurements)
+        result["dual_stream"] = dual_stream(dev, args.sets, max(20, args.steps // 4) if args.dual_stream else max(10, args.steps // 20))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, host_qkv)
     print(json.dumps(result))

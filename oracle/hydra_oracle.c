@@ -99,17 +99,24 @@ int hydra_oracle_attn_varlen(const double* q, const double* k, const double* v, 
     {
 #ifdef _OPENMP
 #pragma omp single
-      used = omp_get_num_threads();
+      used = omp_get_num_threads(); /* one thread writes; the construct ends with a barrier */
 #endif
       double* z = (double*)malloc(sizeof(double) * (size_t)L);
 #pragma omp for schedule(dynamic, 16)
       for (int u = 0; u < units; u++) {
         const int h = u / L, i = u % L, hk = h / g;
-        if (!z) { status = -3; continue; }
+        if (!z) {
+#pragma omp atomic write
+          status = -3;
+          continue;
+        }
         int vis = attend_row(q + ((size_t)(s + i) * n_q_heads + h) * head_dim, k + ((size_t)s * n_kv_heads + hk) * head_dim,
                              v + ((size_t)s * n_kv_heads + hk) * head_dim, L, n_kv_heads * head_dim, head_dim,
                              mask + (size_t)i * L, scale, z, NULL, out + ((size_t)(s + i) * n_q_heads + h) * head_dim);
-        if (vis == 0) status = -4; /* a row with no visible key cannot occur for L >= 1 */
+        if (vis == 0) { /* a row with no visible key cannot occur for L >= 1 */
+#pragma omp atomic write
+          status = -4;
+        }
       }
       free(z);
     }
@@ -135,13 +142,27 @@ int hydra_oracle_attn_rows(const double* q, const double* k, const double* v, co
     int b = -1;
     for (int bb = 0; bb < batch; bb++)
       if (t >= cu[bb] && t < cu[bb + 1]) b = bb;
-    if (b < 0 || h < 0 || h >= n_q_heads) { status = -5; continue; }
+    if (b < 0 || h < 0 || h >= n_q_heads) {
+#pragma omp atomic write
+      status = -5;
+      continue;
+    }
     const int s = cu[b], L = cu[b + 1] - cu[b], i = t - s, hk = h / g;
-    if (probs && L > max_len) { status = -6; continue; }
+    if (probs && L > max_len) {
+#pragma omp atomic write
+      status = -6;
+      continue;
+    }
     /* the explicit mask row for query i of this sequence */
     unsigned char* mrow = (unsigned char*)malloc((size_t)L);
     double* z = (double*)malloc(sizeof(double) * (size_t)L);
-    if (!mrow || !z) { status = -3; free(mrow); free(z); continue; }
+    if (!mrow || !z) {
+#pragma omp atomic write
+      status = -3;
+      free(mrow);
+      free(z);
+      continue;
+    }
     for (int j = 0; j < L; j++) mrow[j] = causal ? (j <= i) : 1;
     double* pr = probs ? probs + (size_t)r * max_len : NULL;
     if (pr) memset(pr, 0, sizeof(double) * (size_t)max_len);
