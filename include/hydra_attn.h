@@ -70,7 +70,7 @@ typedef enum {
  *   workspace   device memory, 16-byte aligned, at least hydra_attn_workspace_bytes(...) bytes.  It
  *        receives the tile work list built on the device from cu_seqlens (entries of
  *        (sequence, KV head, first query tile), grouped into one queue per accelerator die) and
- *        a few counters and flags.  It need not be initialised and may be reused by the next
+ *        a few counters.  It need not be initialised and may be reused by the next
  *        call on the same stream.
  *
  * batch == 0 or total_tokens == 0 returns HYDRA_OK without launching.
@@ -92,7 +92,7 @@ int hydra_attn_varlen_fwd(const void* q, const void* k, const void* v, void* out
  * into `workspace` (same size rule as above).  hydra_attn_varlen_fwd_prebuilt runs the attention
  * kernel against a workspace filled by an earlier hydra_attn_build_worklist call on the same stream
  * (or one that has completed) with the SAME batch, total_tokens, head counts and causal flag.  It
- * reads the work list and uses queue counters and a small flag array inside the workspace (all
+ * reads the work list and uses queue counters inside the workspace (all
  * left zero again when the call's work completes), so two attention calls that share one workspace
  * must not overlap in time.  Arguments, layouts and errors are those of hydra_attn_varlen_fwd.
  */
@@ -132,7 +132,7 @@ int hydra_attn_varlen_fwd_shared(const void* q, const void* k, const void* v, vo
 /*
  * hydra_attn_varlen_fwd for callers that cannot allocate device memory or have none to pass: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The work list,
- * counters and flags live in an array of HYDRA_ATTN_STATIC_SCRATCH_BYTES that is part of the
+ * counters live in an array of HYDRA_ATTN_STATIC_SCRATCH_BYTES that is part of the
  * library's device image (every GPU the library runs on holds its own copy until the process ends);
  * the call allocates and frees nothing, and neither does anything it calls.
  *

@@ -35,76 +35,14 @@
 
 #include <type_traits>
 
+#include "attn_careful.hpp"
+#include "attn_tiles.hpp"
 
 namespace hydra {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
-
-#define HYDRA_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define HYDRA_LDS_BYTE(off) ((__attribute__((address_space(3))) unsigned char*)(uintptr_t)(off))
-#define HYDRA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-
-constexpr int kWaveTileRows = 32;  // query tokens per wave tile
-constexpr int QS = kWaveTileRows / 32;  // 32-query sub-tiles per wave tile
-constexpr int kKvTileRows = 64;    // keys per LDS tile
-constexpr int kWavesPerItem = 4;   // wave tiles per work-list item
-
-// One work-list entry, written by the device prepass from cu_seqlens; it carries everything the
-// kernel needs, so a workgroup starts its loads after a single dependent read.
-//   x = first packed token of the sequence, y = sequence length (0: empty entry past the end of
-//   the list), z = first flattened wave tile of the item (flattened index f = token_tile * group
-//   + head_in_group), w = KV head.
-typedef int4 WorkItem;
-
-constexpr int kXcds = 8;  // accelerator dies; workgroup ids are dealt to them round-robin, each die has its own L2
-
-// Control block at the start of the workspace.  The work list is one array; the entries
-// [xcd_start[x], xcd_start[x + 1]) form the queue of die x and queue_head[x] counts how many of
-// them have been claimed in the current attention call.
-// Every queue head has a 128-byte line of its own: the heads are the only words of the workspace
-// that many workgroups update during the kernel, and claims of different dies must not collide.
-constexpr int kHeadStride = 32;  // int32 words between queue heads
-struct WorkControl {
-  int32_t n_items;
-  int32_t xcd_start[kXcds + 1];
-  int32_t redo_any;      // nonzero when some redo flag is set
-  int32_t careful_done;  // workgroups of the careful kernel that have finished (only counted when redo_any)
-  int32_t reserved[20];
-  int32_t queue_head[kXcds * kHeadStride];  // head of queue x at [x * kHeadStride]; zero between calls
-};
-static_assert(sizeof(WorkControl) == 128 + kXcds * 128, "control block layout");
-
-struct AttnArgs {
-  const uint16_t* q;
-  const uint16_t* k;
-  const uint16_t* v;
-  uint16_t* out;
-  int64_t q_stride, k_stride, v_stride;  // elements per token
-  const int32_t* cu_seqlens;
-  const WorkItem* items;
-  WorkControl* ctrl;
-  int32_t* redo_flags;  // one per work item; set when the item must be recomputed carefully
-  int32_t n_q_heads;
-  int32_t group;     // n_q_heads / n_kv_heads
-  float scale_log2;  // softmax_scale * log2(e)
-};
-
 template <int D>
-struct TileGeom {
-  static constexpr int kRowBytes = D * 2;
-  static constexpr int kChunks = kRowBytes / 16;                 // 16-byte pieces per row
-  static constexpr int kQkSteps = D / 16;                        // 32x32x16 steps of the QK contraction
-  static constexpr int kPvChunks = (D + 31) / 32;                // 32-wide output column blocks of PV
-  static constexpr int kTileBytes = kKvTileRows * kRowBytes;     // one K or V tile
-  static constexpr int kLoadInstr = kTileBytes / 1024;           // wave-wide 16 B/lane loads per tile
+struct TileGeom : RowGeom<D> {
+  using RowGeom<D>::kTileBytes;
   // K tiles and V tiles each live in a ring of kRing LDS tiles; loads run kRing - 1 tiles ahead of use
   // (a tile's slot is free again after the barrier that ends the iteration consuming it)
   static constexpr int kRing = 2;
@@ -118,47 +56,6 @@ struct TileGeom {
   static constexpr int kOnesAt = 2 * kRing * kTileBytes + 64;    // (+ slack behind the last V tile)
   static constexpr int kLdsBytes = kOnesAt + kOnesBytes;
 };
-
-// XOR swizzles of the 16-byte chunk index inside an LDS row.  Chosen so that the 16 lanes the
-// LDS serves together hit 16 different bank groups: for K, lanes read the same logical chunk of
-// 16 consecutive rows; for V, a transposing read touches 4 consecutive rows x 64 bytes.
-template <int D>
-__device__ __forceinline__ int k_swizzle(int row, int chunk) {
-  if constexpr (D == 128) return chunk ^ (row & 15);
-  else if constexpr (D == 64) return chunk ^ ((row >> 1) & 7);
-  else return chunk ^ ((row >> 3) & 1);
-}
-template <int D>
-__device__ __forceinline__ int v_swizzle(int row, int chunk) {
-  if constexpr (D == 128) return chunk ^ ((row & 3) << 2);
-  else if constexpr (D == 64) return chunk ^ (((row >> 1) & 1) << 2);
-  else return chunk;
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Exchange between the two 32-lane halves with v_permlane32_swap, which swaps the upper half
-// of its first register with the lower half of its second.  Starting from two copies of x:
-//   r0 = x of the low-half lane of the pair (in both lanes), r1 = x of the high-half lane.
-// Written as inline assembly so that both registers are explicit read-write operands; the
-// s_nop padding covers the wait states between VALU writes/reads and the lane swap, which the
-// compiler's hazard pass cannot see inside an asm block.
-__device__ __forceinline__ void own_and_other_half(float x, float& r0, float& r1) {
-  float a = x, b = x;
-  asm volatile("s_nop 3\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 3" : "+v"(a), "+v"(b));
-  r0 = a;
-  r1 = b;
-}
-__device__ __forceinline__ float max_with_other_half(float x) {
-  float r0, r1;
-  own_and_other_half(x, r0, r1);
-  return fmaxf(r0, r1);
-}
-__device__ __forceinline__ float sum_with_other_half(float x) {
-  float r0, r1;
-  own_and_other_half(x, r0, r1);
-  return r0 + r1;
-}
 
 // Everything below uses gfx950-only types and builtins, so the host pass of hipcc only sees the
 // kernel's declaration (it still emits the launch stub).
@@ -301,12 +198,26 @@ __device__ __forceinline__ void s_results_to_valu(f32x16_t (&S)[2]) { asm volati
 // Scheduling hints: keep the listed instruction classes in this order inside the current region.
 #define HYDRA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Every workgroup of the grid ends up making exactly ONE failing claim on every queue: on its own when that
+// runs dry, on each of the others while it looks for work to steal (a queue found empty is not asked again).
+// A queue of n items has therefore been asked n + (workgroups) times when the kernel ends, and the workgroup
+// whose claim returns position n + (workgroups) - 1 is the last that will ever touch that head in this call: it
+// puts the head back to zero, so that the next attention call on the same work list (the next layer of the same
+// batch) finds a clean control block.  No counter of finished workgroups is needed, and no launch to tidy up.
+// Called by the lane that holds the position.
+__device__ __forceinline__ void reset_head_if_last(WorkControl* ctrl, int y, int pos, int n_items) {
+  if (pos == n_items + (int)gridDim.x - 1) atomicExch(&ctrl->queue_head[y * kHeadStride], 0);
+}
+
 // Claims the next unclaimed entry of queue y.  Called by all lanes of ONE wave; returns the list
 // index, or -1 when the queue is empty.
 __device__ __forceinline__ int claim_from(WorkControl* ctrl, int y, int lane) {
   const int begin = ctrl->xcd_start[y], end = ctrl->xcd_start[y + 1];
   int pos = 0;
-  if (lane == 0) pos = atomicAdd(&ctrl->queue_head[y * kHeadStride], 1);
+  if (lane == 0) {
+    pos = atomicAdd(&ctrl->queue_head[y * kHeadStride], 1);
+    reset_head_if_last(ctrl, y, pos, end - begin);
+  }
   pos = __builtin_amdgcn_readfirstlane(pos);
   return pos < end - begin ? begin + pos : -1;
 }
@@ -347,9 +258,6 @@ struct StepFrags {
 #endif
 constexpr float kMaxRowSum = 1.0995116e12f;  // 2^40: largest row sum (relative to the reference) the fast kernel accepts
 
-// Persistent workgroups per compute unit (= waves per SIMD): as many as the register file holds.
-template <int D>
-constexpr int kWorkgroupsPerCu = D == 64 ? 3 : 2;
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroupsPerCu<D>, kWorkgroupsPerCu<D>))) void attn_fwd_kernel(const AttnArgs a) {
@@ -371,7 +279,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // die this workgroup runs on (hardware id register XCC_ID, bits 3:0)
   const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
-  __shared__ __attribute__((aligned(16))) int s_claim[8];
+  __shared__ __attribute__((aligned(16))) int s_claim[4];
+  // An item whose exponentials left the fast path's range: {flag, first token, length, first wave tile, KV head},
+  // posted by the waves that noticed, acted upon by the whole workgroup at the top of its next round.
+  __shared__ __attribute__((aligned(16))) int s_redo[8];
+  if (threadIdx.x == 0) s_redo[0] = 0;
   if constexpr (G::kSumsFromMatrixUnit) {
     static_assert((R - 1) * G::kTileBytes + kKvTileRows * ROWB - 8 * ROWB + 8 <= G::kOnesBytes, "a V fragment read stays inside the ones");
     for (int i = threadIdx.x * 16; i < G::kOnesBytes; i += 256 * 16)
@@ -395,7 +307,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       s_claim[1] = it.y;
       s_claim[2] = it.z;
       s_claim[3] = it.w;
-      s_claim[4] = idx;
     }
   };
   const int own_begin = a.ctrl->xcd_start[xcc], own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
@@ -436,6 +347,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 
   for (;;) {  // one work item per round
   __syncthreads();
+  if (__builtin_expect(__builtin_amdgcn_readfirstlane(s_redo[0]) != 0, 0)) {
+    // The previous round's item has to be redone carefully.  Its (wrong) output rows are already stored and are
+    // overwritten by the same waves; the loads of the next item's Q, in flight into the V ring, are waited for
+    // first (the routine takes both rings as its stages) and issued again afterwards.
+    const int64_t r_start = __builtin_amdgcn_readfirstlane(s_redo[1]);
+    const int r_len = __builtin_amdgcn_readfirstlane(s_redo[2]);
+    const int r_f0 = __builtin_amdgcn_readfirstlane(s_redo[3]);
+    const int r_kv = __builtin_amdgcn_readfirstlane(s_redo[4]);
+    wait_all_loads();
+    __syncthreads();
+    if (threadIdx.x == 0) s_redo[0] = 0;
+    careful::run_item<D, CAUSAL>(a, r_start, r_len, r_f0, r_kv, k_ring);
+    q_ahead = false;
+  }
   // Everything derived from the lane number is recomputed in every round (the empty statement hides
   // the value from the optimiser): kept across rounds, dozens of such lane constants would sit in
   // registers through the hot loop, which has none to spare.
@@ -455,7 +380,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int seq_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
   const int f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
   const int kv_head = __builtin_amdgcn_readfirstlane(s_claim[3]);
-  const int item_idx = __builtin_amdgcn_readfirstlane(s_claim[4]);
   if (seq_len == 0) break;
   // Thread 0: position claimed in this die's queue for the next round.  (Written as a per-thread
   // condition, and read below by every wave, on purpose: the compiler tracks outstanding memory
@@ -561,8 +485,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // one fused multiply-add per score, p = exp2(score * c - reference * c), c = softmax_scale * log2 e.
   // That is exact as long as the exponentials stay far from the end of the fp32
   // range: a wave whose row sums (which bound every single exponential) exceed kMaxRowSum, or are
-  // not finite, flags its work item, and the flagged items are recomputed afterwards by the careful
-  // kernel, which rescales at every tile.  (bf16 activations lead the first block's maximum by a few
+  // not finite, posts its work item for the careful routine (attn_careful.hpp), which rescales at every tile
+  // and which the workgroup runs at the top of its next round.  (bf16 activations lead the first block's maximum by a few
   // powers of two at most.  Below the limit the unnormalised output is bounded by 2^40 times the sum
   // of |V| over the keys, so it cannot overflow for |V| up to 10^20.)
   float nref[QS];        // -reference * c of this lane's query row
@@ -816,6 +740,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   if (wave == 0) {
     // (own queue empty: an empty claim is posted, and the top of the next round goes stealing)
     const int idx = pos < own_count ? own_begin + pos : -1;
+    if (lane == 0) reset_head_if_last(a.ctrl, xcc, pos, own_count);
     // The item itself travels memory -> LDS on its own (one more direct-to-LDS load, lane 0 only):
     // it is complete when this wave's last wait of the round (for zero loads in flight) has
     // passed, and the barrier after that wait makes it visible to the other waves.  Every wave
@@ -837,7 +762,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
         s_claim[2] = 0;
         s_claim[3] = 0;
       }
-      s_claim[4] = idx;
     }
   }
 
@@ -908,7 +832,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     __syncthreads();
   }
   __builtin_amdgcn_s_setprio(0);
-  // a row sum out of the safe range somewhere in this wave's rows: have the item recomputed
+  // a row sum out of the safe range somewhere in this wave's rows: have the item recomputed (top of the next round)
   if (NB > 0) {
     bool too_far = false;
 #pragma unroll
@@ -918,8 +842,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       too_far = too_far || !(row_sum[qs] <= kMaxRowSum);
     }
     if (__builtin_amdgcn_ballot_w64(too_far) != 0 && lane == 0) {
-      a.redo_flags[item_idx] = 1;
-      a.ctrl->redo_any = 1;
+      s_redo[1] = (int)seq_start;
+      s_redo[2] = seq_len;
+      s_redo[3] = f0;
+      s_redo[4] = kv_head;
+      s_redo[0] = 1;
     }
   }
   // The next item (posted during this round; the last iteration's wait and barrier made it visible):

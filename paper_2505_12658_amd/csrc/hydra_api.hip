@@ -8,7 +8,6 @@
 #include <tuple>
 
 #include "../../include/hydra_attn.h"
-#include "attn_careful.hpp"
 #include "attn_fwd.hpp"
 #include "attn_paged.hpp"
 #include "kv_write.hpp"
@@ -44,8 +43,8 @@ unsigned compute_units() {
   return (unsigned)n;
 }
 
-// The fast kernel over the whole work list, then the careful kernel over whatever it flagged
-// (normally nothing: a few workgroups read the flags and leave).
+// One launch: the persistent workgroups drain the work list (an item whose exponentials leave the
+// fast path's range is redone on the spot, by the same workgroup, with the careful routine).
 template <int D>
 hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned compute_units, int workgroups_per_cu, hipStream_t stream) {
   // two or three persistent workgroups per compute unit (each takes its share of registers and LDS):
@@ -55,16 +54,8 @@ hipError_t launch_attn(bool causal, const hydra::AttnArgs& args, unsigned comput
   const unsigned per_cu = workgroups_per_cu > 0 && workgroups_per_cu < hydra::kWorkgroupsPerCu<D> ? (unsigned)workgroups_per_cu
                                                                                                   : (unsigned)hydra::kWorkgroupsPerCu<D>;
   const unsigned grid = per_cu * compute_units;
-  const unsigned careful_grid = compute_units;
-  hipError_t err;
-  if (causal) {
-    err = launch(hydra::attn_fwd_kernel<D, true>, dim3(grid), dim3(256), stream, args);
-    if (err == hipSuccess) err = launch(hydra::careful::attn_fwd_careful_kernel<D, true>, dim3(careful_grid), dim3(256), stream, args);
-  } else {
-    err = launch(hydra::attn_fwd_kernel<D, false>, dim3(grid), dim3(256), stream, args);
-    if (err == hipSuccess) err = launch(hydra::careful::attn_fwd_careful_kernel<D, false>, dim3(careful_grid), dim3(256), stream, args);
-  }
-  return err;
+  return causal ? launch(hydra::attn_fwd_kernel<D, true>, dim3(grid), dim3(256), stream, args)
+                : launch(hydra::attn_fwd_kernel<D, false>, dim3(grid), dim3(256), stream, args);
 }
 
 // Bytes of one partial result of the paged kernel's packed-rows form.
@@ -147,15 +138,14 @@ int hydra_attn_build_worklist(const int32_t* cu_seqlens, int32_t batch, int32_t 
   int32_t* sorted_seq = reinterpret_cast<int32_t*>(ws + lay.sorted_at);
   int32_t* queue_prefix = reinterpret_cast<int32_t*>(ws + lay.prefix_at);
   hydra::WorkItem* items = reinterpret_cast<hydra::WorkItem*>(ws + lay.items_at);
-  int32_t* flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   const int group = n_q_heads / n_kv_heads;
   const int tail_items = hydra::tail_sort_items(group, head_dim);
   const dim3 grid(hydra::prepass_workgroups(lay.capacity)), block(hydra::kPrepassThreads);
   const hipError_t err =
       causal ? launch(hydra::build_worklist_kernel<true>, grid, block, s, cu_seqlens, batch, n_kv_heads, group, ctrl, sorted_seq, queue_prefix,
-                      (int)lay.rows, items, flags, (int)lay.capacity, tail_items)
+                      (int)lay.rows, items, (int)lay.capacity, tail_items)
              : launch(hydra::build_worklist_kernel<false>, grid, block, s, cu_seqlens, batch, n_kv_heads, group, ctrl, sorted_seq, queue_prefix,
-                      (int)lay.rows, items, flags, (int)lay.capacity, tail_items);
+                      (int)lay.rows, items, (int)lay.capacity, tail_items);
   return err == hipSuccess ? HYDRA_OK : HYDRA_ERR_LAUNCH;
 }
 
@@ -218,7 +208,6 @@ int attn_prebuilt(const void* q, const void* k, const void* v, void* out, int64_
   args.cu_seqlens = cu_seqlens;
   args.items = reinterpret_cast<const hydra::WorkItem*>(ws + lay.items_at);
   args.ctrl = reinterpret_cast<hydra::WorkControl*>(ws);
-  args.redo_flags = reinterpret_cast<int32_t*>(ws + lay.flags_at);
   args.n_q_heads = n_q_heads;
   args.group = n_q_heads / n_kv_heads;
   // A scale of exactly 0 is replaced by a vanishing positive one: every visible key still gets

@@ -44,14 +44,10 @@ inline int tail_sort_items(int group, int head_dim) {
 //   int32 sorted_seq[B]                  sequences by descending length
 //   int32 queue_prefix[kXcds][rows]      rows = ceil(B * Hkv / 8): items before the pair of (row, queue) in its queue
 //   WorkItem items[capacity]             16-byte aligned
-//   int32 redo_flags[capacity]           all zero between calls; the fast attention kernel sets the flag
-//                                        of an item it cannot finish exactly, the careful kernel redoes
-//                                        the item and clears it
 struct WorkspaceLayout {
   size_t sorted_at;  // bytes
   size_t prefix_at;  // bytes
   size_t items_at;   // bytes
-  size_t flags_at;   // bytes
   size_t rows;       // pair rows
   size_t capacity;   // items
   size_t total;      // bytes
@@ -72,8 +68,7 @@ inline WorkspaceLayout workspace_layout(int64_t batch, int64_t total_tokens, int
   const size_t end = w.prefix_at + w.rows * kXcds * 4;
   w.items_at = (end + 15) & ~(size_t)15;
   w.capacity = item_capacity(batch, total_tokens, n_q_heads, n_kv_heads);
-  w.flags_at = w.items_at + w.capacity * sizeof(WorkItem);
-  w.total = w.flags_at + w.capacity * sizeof(int32_t);
+  w.total = w.items_at + w.capacity * sizeof(WorkItem);
   return w;
 }
 
@@ -95,7 +90,7 @@ template <bool CAUSAL>
 __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const int32_t* __restrict__ cu, int batch, int n_kv_heads, int group,
                                                                          WorkControl* __restrict__ ctrl, int32_t* __restrict__ sorted_seq,
                                                                          int32_t* __restrict__ queue_prefix_global, int rows,
-                                                                         WorkItem* __restrict__ items, int32_t* __restrict__ redo_flags,
+                                                                         WorkItem* __restrict__ items,
                                                                          int capacity, int tail_items) {
   __shared__ int s_len[kPrepassLdsSeqs];
   __shared__ int s_start[kPrepassLdsSeqs];
@@ -111,12 +106,7 @@ __global__ __launch_bounds__(kPrepassThreads) void build_worklist_kernel(const i
   // out over the grid (step 3), and workgroup x < 8 also orders the tail of queue x (step 4).  Workgroup 0
   // writes the control block.
   const bool leader = blockIdx.x == 0;
-  for (int i = blockIdx.x * kPrepassThreads + tid; i < capacity; i += gridDim.x * kPrepassThreads) redo_flags[i] = 0;
   if (leader && tid < kXcds) ctrl->queue_head[tid * kHeadStride] = 0;
-  if (leader && tid == 0) {
-    ctrl->redo_any = 0;
-    ctrl->careful_done = 0;
-  }
 
   // Small batches (the normal case) are handled entirely in LDS after one read of cu_seqlens;
   // the global arrays are only used for what does not fit.

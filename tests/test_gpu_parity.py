@@ -128,9 +128,9 @@ def test_out_of_range_rows_untouched_and_deterministic():
 @pytest.mark.parametrize("d", [64, 80, 128])
 def test_large_scores_take_careful_path(d, causal):
     """Keys planted after the first key block whose scores lead the block-0 maximum by far more than
-    the fast kernel's range (row sums beyond 2^40 times the reference term): it flags the affected work items and the careful kernel redoes them (if it
-    did not, the flagged rows would be inf/NaN or wrong).  Afterwards the flag words in the
-    workspace are all zero again, and a second call on the same workspace gives the same bits."""
+    the fast path's range (row sums beyond 2^40 times the reference term): the workgroup that notices redoes the
+    item with the careful routine (if it did not, the affected rows would be inf/NaN or wrong).  Afterwards the
+    queue heads in the workspace are all zero again, and a second call on the same workspace gives the same bits."""
     hydra = _hydra()
     w = si.custom([100, 257, 40, 64], 4, 2, d, causal, seed=77)
     q, k, v = si.make_qkv(w)
@@ -150,16 +150,10 @@ def test_large_scores_take_careful_path(d, causal):
     z = w.softmax_scale * 64.0 * _f64(q).sum(axis=-1)
     assert (z * 1.4427 > 100).sum() > 50
     _check(out, want)
-    # workspace: control block (int32 [10], [11] = summary word, counter; queue heads at [32 + 32 x]),
-    # sorted sequences, queue prefixes, then 16-byte items and one int32 flag per item up to the end
+    # workspace: control block with the queue heads at int32 [32 + 32 x], back at zero after every call
     words = ws.cpu().numpy().view(np.int32)
     n_items = int(words[0])
-    assert n_items > 0 and words[10] == 0 and words[11] == 0 and (words[32:32 + 256:32] == 0).all()
-    rows = (w.batch * 2 + 7) // 8
-    items_at = (1152 + 4 * w.batch + 32 * rows + 15) // 16 * 16
-    capacity = (ws.numel() - items_at) // 20
-    assert capacity >= n_items
-    assert (words[(items_at + 16 * capacity) // 4:] == 0).all()
+    assert n_items > 0 and (words[32:32 + 256:32] == 0).all()
     again = torch.empty_like(qd)
     hydra.hydra_attn_varlen_fwd_prebuilt(qd, kd, vd, cu, w.max_seqlen, causal, w.softmax_scale, again, ws)
     torch.cuda.synchronize()
