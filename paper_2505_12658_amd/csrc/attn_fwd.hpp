@@ -61,10 +61,11 @@ struct TileGeom : RowGeom<D> {
 // kernel's declaration (it still emits the launch stub).
 #if defined(__HIP_DEVICE_COMPILE__)
 // Loads of one 64-row K or V tile, global -> LDS, 16 bytes per lane, through a buffer resource
-// that covers exactly the rows of this sequence and KV head from the tile's first row on: rows
-// past the end of the sequence are out of range and arrive as zeros (they are masked later;
-// zeros keep V finite).  The per-lane offset is fixed for the whole kernel; the tile advances
-// through the descriptor's base address.
+// that covers exactly the rows of this sequence and KV head: rows past the end of the sequence are out
+// of range and arrive as zeros (they are masked later; zeros keep V finite).  The descriptor and the
+// per-lane offset are fixed for the whole item; the tile advances through the instruction's scalar
+// offset, which the hardware's range check takes into account (a scalar offset beyond the end of the
+// buffer puts every lane out of range).
 //
 // The load is issued from inline assembly on purpose: when the compiler knows that vector-memory
 // loads write LDS, it makes every later LDS read wait for ALL outstanding loads (vmcnt 0), which
@@ -78,14 +79,12 @@ struct TileLoader {
   using G = TileGeom<D>;
   static constexpr int kPerWave = (G::kLoadInstr + 3) / 4;
   // When four load instructions cover a whole number of rows, the lane offsets of a wave's loads
-  // differ by a constant (the swizzle repeats), which goes into the instruction's scalar offset:
+  // differ by a constant (the swizzle repeats), which also goes into the scalar offset:
   // one offset register instead of kPerWave.
   static constexpr bool kUniformStep = (4 * 64) % G::kChunks == 0 && ((4 * 64) / G::kChunks) % 16 == 0;
   static constexpr int kOffsets = kUniformStep ? 1 : kPerWave;
-  // Tiles are issued strictly in order (0, 1, 2, ...), so the descriptor of the next tile is kept
-  // in scalar registers and advanced by one tile after every issue.
-  uint32_t base_lo, base_hi;    // address of the first row of the next tile
-  uint32_t left;                // bytes from there to the end of the sequence's last valid row (0: past the end)
+  u32x4_t rsrc;                 // the sequence's rows of this KV head, from the first row to the end of the last
+  uint32_t tile_off;            // bytes from the first row of the sequence to the first row of the next tile
   uint32_t tile_stride;         // bytes between first rows of consecutive tiles
   uint32_t lane_off[kOffsets];  // bytes from the first row of a tile
   uint32_t step_bytes;          // kUniformStep: bytes between the rows of consecutive loads of this wave
@@ -97,9 +96,11 @@ struct TileLoader {
     __builtin_assume(wave >= 0 && wave < kWavesPerItem);
     const uint32_t row_bytes = (uint32_t)(stride * 2);
     const uint64_t first_row = (uint64_t)(uintptr_t)(base + seq_start * stride + kv_head * D);
-    base_lo = __builtin_amdgcn_readfirstlane((uint32_t)first_row);
-    base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(first_row >> 32));
-    left = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2));
+    rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)first_row);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(first_row >> 32) & 0xffffu);
+    rsrc[2] = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)(seq_len - 1) * stride + D) * 2));
+    rsrc[3] = 0x00020000u;
+    tile_off = 0;
     tile_stride = __builtin_amdgcn_readfirstlane((uint32_t)kKvTileRows * row_bytes);
     step_bytes = __builtin_amdgcn_readfirstlane((uint32_t)((4 * 64) / G::kChunks) * row_bytes);
 #pragma unroll
@@ -110,52 +111,24 @@ struct TileLoader {
       lane_off[u] = (uint32_t)row * row_bytes + chunk * 16;
     }
   }
-  // number of load instructions this wave issues per tile
-  __device__ __forceinline__ int per_tile() const {
-    int n = 0;
-#pragma unroll
-    for (int u = 0; u < kPerWave; ++u) n += (wave + 4 * u < G::kLoadInstr);
-    return n;
-  }
-  // Buffer descriptor of the NEXT tile.  wanted == false: a descriptor of zero bytes (every lane is
-  // out of range: nothing is fetched, and the LDS slot receives zeros).
-  __device__ __forceinline__ u32x4_t next_descriptor(bool wanted = true) const {
-    u32x4_t rsrc;
-    // (the values are uniform by construction; the intrinsic states it for the register allocator)
-    rsrc[0] = __builtin_amdgcn_readfirstlane(base_lo);
-    rsrc[1] = __builtin_amdgcn_readfirstlane(base_hi & 0xffffu);
-    rsrc[2] = __builtin_amdgcn_readfirstlane(wanted ? left : 0u);
-    rsrc[3] = 0x00020000u;
-    return rsrc;
-  }
   // Issues load u (0 .. kPerWave - 1) of this wave's share of the next tile; lds_dst: LDS byte address
   // of the tile's ring slot.
-  __device__ __forceinline__ void issue_piece(int u, const u32x4_t& rsrc, uint32_t lds_dst) const {
+  __device__ __forceinline__ void issue_piece(int u, uint32_t lds_dst) const {
     const int instr = wave + 4 * u;
     if (instr < G::kLoadInstr) {
       // (m0 is reserved: the compiler only ever sets it immediately before an instruction of its own that reads it)
       const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + instr * 1024);
-      if constexpr (kUniformStep) {
-        const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)u * step_bytes);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(m0), "v"(lane_off[0]), "s"(rsrc), "s"(soff));
-      } else {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off[u]), "s"(rsrc));
-      }
+      const uint32_t soff = __builtin_amdgcn_readfirstlane(tile_off + (kUniformStep ? (uint32_t)u * step_bytes : 0u));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                   :
+                   : "s"(m0), "v"(lane_off[kUniformStep ? 0 : u]), "s"(rsrc), "s"(soff));
     }
   }
-  // Moves on to the tile after the next one.
-  __device__ __forceinline__ void advance() {
-    const uint32_t lo = base_lo + tile_stride;
-    base_hi += lo < base_lo ? 1u : 0u;
-    base_lo = lo;
-    left = left > tile_stride ? left - tile_stride : 0u;
-  }
-  // Issues all of this wave's loads of the next tile at once.
+  // Issues all of this wave's loads of the next tile at once and moves on to the tile after it.
   __device__ __forceinline__ void issue_next(uint32_t lds_dst) {
-    const u32x4_t rsrc = next_descriptor();
 #pragma unroll
-    for (int u = 0; u < kPerWave; ++u) issue_piece(u, rsrc, lds_dst);
-    advance();
+    for (int u = 0; u < kPerWave; ++u) issue_piece(u, lds_dst);
+    tile_off += tile_stride;
   }
 };
 
