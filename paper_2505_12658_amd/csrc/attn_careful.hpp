@@ -71,7 +71,11 @@ __device__ __forceinline__ void run_item(const AttnArgs& a, int64_t seq_start, i
   const int n_wave_tiles = n_tok_tiles * a.group;
   const int n_kv_tiles = (seq_len + kKvTileRows - 1) / kKvTileRows;
 
-  const int lane = threadIdx.x & 63;
+  // (The empty statement hides the lane number from the optimiser: the routine is inlined into a cold branch of
+  // the packed kernel's item loop, and everything that depends only on the lane would otherwise be computed
+  // ahead of that loop and kept, in registers the hot loop does not have, i.e. in scratch memory.)
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
 
