@@ -339,6 +339,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // registers through the hot loop, which has none to spare.
   int lane = lane_id;
   asm volatile("" : "+v"(lane));
+  __builtin_assume(lane >= 0 && lane < 64);  // (divisions of lane-derived indices by constants become shifts)
   const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
   if (__builtin_amdgcn_readfirstlane(s_claim[1]) == 0) {
     // Nothing left in this die's queue: take an item from another die's queue.  This is done here, with

@@ -25,7 +25,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "attn_fwd.hpp"
+#include "attn_tiles.hpp"
 
 namespace hydra {
 namespace paged {
@@ -73,14 +73,10 @@ __device__ __forceinline__ void split_range(int n_halves, int per, int s, int& b
 }
 
 template <int D>
-struct StageGeom {
-  static constexpr int kRowBytes = D * 2;
-  static constexpr int kChunks = kRowBytes / 16;
-  static constexpr int kQkSteps = D / 16;
-  static constexpr int kPvChunks = (D + 31) / 32;
-  static constexpr int kTileBytes = kKvTileRows * kRowBytes;  // one K or V tile
-  static constexpr int kStageBytes = 2 * kTileBytes;          // K then V
-  static constexpr int kLoadInstr = kTileBytes / 1024;
+struct StageGeom : RowGeom<D> {
+  using RowGeom<D>::kTileBytes;
+  using RowGeom<D>::kPvChunks;
+  static constexpr int kStageBytes = 2 * kTileBytes;  // K then V
   // A wave's slot in the packed-rows form: a stage of a HALF tile (32 keys of K, then of V) during the loop,
   // its unnormalised output (kPvChunks * 16 registers x 64 lanes x 4 bytes) for the merge.  Four slots; the
   // wave-tile form uses the same memory as its two 64-key stages.
