@@ -273,10 +273,10 @@ def test_worklist_covers_every_tile_once_and_ends_with_cheap_items(hq, hkv, d, c
         assert all(a >= b for a, b in zip(t, t[1:])), (x, t)
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_ragged_batches(seed):
     """Seeded random batches (number of sequences, lengths with zeros and tile-boundary values mixed in, head
-    grouping, head_dim, mask) against the C oracle, whole output."""
+    grouping, head_dim, mask, softmax scale off the usual 1/sqrt(d)) against the C oracle, whole output."""
     rng = np.random.default_rng(1000 + seed)
     hq, hkv = [(1, 1), (2, 1), (4, 2), (7, 1), (8, 8), (6, 3)][int(rng.integers(6))]
     d = [64, 80, 128][int(rng.integers(3))]
@@ -288,8 +288,9 @@ def test_random_ragged_batches(seed):
         lengths[0] = 5
     w = si.custom(lengths, hq, hkv, d, causal, seed=seed)
     q, k, v = si.make_qkv(w)
-    out = _run_gpu(w, q, k, v)
-    _check(out, c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, causal, w.softmax_scale))
+    scale = w.softmax_scale * float(rng.choice([1.0, 1.0, 0.37, 1.9]))
+    out = _run_gpu(w, q, k, v, scale=scale)
+    _check(out, c_oracle.attn_varlen(_f64(q), _f64(k), _f64(v), w.cu_seqlens, causal, scale))
 
 
 def test_many_short_sequences():
