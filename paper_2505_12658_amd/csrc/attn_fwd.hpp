@@ -141,7 +141,7 @@ __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt
 // splits the budget in two halves as soon as one is needed), so scores and output accumulators
 // live in ordinary registers, where the softmax and the epilogue read them directly.
 // O += V^T P goes through the compiler's builtin, which inserts the wait states the readers of the
-// result need.  S = K Q'^T is written as inline assembly: measured faster at head_dim 128 (the
+// result need.  S = K Q^T is written as inline assembly: measured faster at head_dim 128 (the
 // compiler pads every builtin with its own wait states and is freer to move it).  The compiler does
 // not see these as matrix instructions, so
 //   - s_results_to_valu() supplies the wait states between the last of them and the first reader of
