@@ -232,9 +232,23 @@ struct StepFrags {
 constexpr float kMaxRowSum = 1.0995116e12f;  // 2^40: largest row sum (relative to the reference) the fast kernel accepts
 
 
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroupsPerCu<D>, kWorkgroupsPerCu<D>))) void attn_fwd_kernel(const AttnArgs a) {
+// Where a workgroup's items and their K/V rows come from.  The packed kernel (below) takes items from the work
+// list's queues and K/V rows from the packed batch; the paged kernel runs ONE item per call, handed over in its
+// source object, with K/V rows gathered from cache pages and queries that are the LAST q_len positions of a
+// context of kv_len keys (see attn_paged.hpp for that source).
+struct PackedSource {
+  static constexpr bool kPaged = false;
+  template <int D>
+  struct Gather {};  // (the paged source's K/V gatherer; the packed rows use two TileLoaders)
+};
+
 #if defined(__HIP_DEVICE_COMPILE__)
+// The item loop of a workgroup (4 waves).  smem: TileGeom<D>::kLdsBytes bytes of LDS, 1024-aligned; s_claim: 4
+// ints, s_redo: 8 ints of LDS.  Packed source: runs until the queues are empty.  Paged source: runs the source's
+// item and returns whether its row sums left the fast path's range (same value in every thread; the caller then
+// recomputes the item with its own careful routine).
+template <int D, bool CAUSAL, class Src>
+__device__ __forceinline__ bool attn_item_loop(const AttnArgs& a, const Src& src, unsigned char* smem, int* s_claim, int* s_redo) {
   using G = TileGeom<D>;
   constexpr int KS = G::kQkSteps;
   constexpr int CC = G::kPvChunks;
@@ -242,7 +256,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   constexpr int NQ = KS;      // QK work units per key block: step s = one K fragment read + 2 MFMAs (qs = 0, 1)
   constexpr int NP = 2 * CC;  // PV work units per key block: (s2, cc) = one V^T fragment + 2 MFMAs
   constexpr int PF = kFragsAhead<D>;
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
   // LDS: K ring then V ring; tile t of either lives in ring slot t % kRing.
   constexpr int R = G::kRing, PD = G::kPrefetch;
   const uint32_t k_ring = (uint32_t)(uintptr_t)HYDRA_LDS_PTR(smem);  // LDS byte addresses
@@ -252,10 +265,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // die this workgroup runs on (hardware id register XCC_ID, bits 3:0)
   const int xcc = (int)__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1);
-  __shared__ __attribute__((aligned(16))) int s_claim[4];
-  // An item whose exponentials left the fast path's range: {flag, first token, length, first wave tile, KV head},
-  // posted by the waves that noticed, acted upon by the whole workgroup at the top of its next round.
-  __shared__ __attribute__((aligned(16))) int s_redo[8];
+  // s_redo: an item whose exponentials left the fast path's range: {flag, first token, length, first wave tile, KV
+  // head}, posted by the waves that noticed, acted upon by the whole workgroup at the top of its next round.
   if (threadIdx.x == 0) s_redo[0] = 0;
   if constexpr (G::kSumsFromMatrixUnit) {
     static_assert((R - 1) * G::kTileBytes + kKvTileRows * ROWB - 8 * ROWB + 8 <= G::kOnesBytes, "a V fragment read stays inside the ones");
@@ -282,7 +293,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       s_claim[3] = it.w;
     }
   };
-  const int own_begin = a.ctrl->xcd_start[xcc], own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
+  int own_begin = 0, own_count = 0;
+  if constexpr (!Src::kPaged) {
+    own_begin = a.ctrl->xcd_start[xcc];
+    own_count = a.ctrl->xcd_start[xcc + 1] - own_begin;
+  }
   // Q: a wave's 32 rows come in with direct-to-LDS loads that cover whole rows (loaded straight
   // into the B-operand register layout, one instruction would touch 32 different rows: one address
   // cycle per row in the memory pipeline), into a private staging area in K-tile layout, and are
@@ -316,10 +331,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   bool q_ahead = false;      // the current item's Q loads were issued at the end of the previous round
   bool own_empty = false;    // this die's queue has run out (same value in all waves)
   uint32_t empty_mask = 0;   // wave 0: other dies' queues found empty
-  if (wave == 0) post_claim(claim_from(a.ctrl, xcc, lane_id));
+  if constexpr (!Src::kPaged) {
+    if (wave == 0) post_claim(claim_from(a.ctrl, xcc, lane_id));
+  }
 
   for (;;) {  // one work item per round
   __syncthreads();
+  if constexpr (!Src::kPaged)
   if (__builtin_expect(__builtin_amdgcn_readfirstlane(s_redo[0]) != 0, 0)) {
     // The previous round's item has to be redone carefully.  Its (wrong) output rows are already stored and are
     // overwritten by the same waves; the loads of the next item's Q, in flight into the V ring, are waited for
@@ -341,6 +359,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   asm volatile("" : "+v"(lane));
   __builtin_assume(lane >= 0 && lane < 64);  // (divisions of lane-derived indices by constants become shifts)
   const int m = lane & 31, hf = lane >> 5, sl = lane & 15, grp = (lane >> 4) & 1;
+  if constexpr (!Src::kPaged)
   if (__builtin_amdgcn_readfirstlane(s_claim[1]) == 0) {
     // Nothing left in this die's queue: take an item from another die's queue.  This is done here, with
     // the workgroup idle, and synchronously (two memory round trips), not ahead of time like the claims
@@ -350,17 +369,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
     if (wave == 0) post_claim(steal_item(a.ctrl, xcc, (int)(blockIdx.x >> 3), lane_id, empty_mask));
     __syncthreads();
   }
-  const int64_t seq_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
-  const int seq_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
-  const int f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
-  const int kv_head = __builtin_amdgcn_readfirstlane(s_claim[3]);
-  if (seq_len == 0) break;
+  // The item: `seq_len` query rows that start at packed token `seq_start`, and `kv_len` keys; query row i sees
+  // keys 0 .. shift + i (causal).  Packed batch: the keys are the sequence's own rows, shift = 0.
+  int64_t seq_start;
+  int seq_len, f0, kv_head;
+  if constexpr (Src::kPaged) {
+    seq_start = src.q_start;
+    seq_len = src.q_len;
+    f0 = src.f0;
+    kv_head = src.kv_head;
+  } else {
+    seq_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
+    seq_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
+    f0 = __builtin_amdgcn_readfirstlane(s_claim[2]);
+    kv_head = __builtin_amdgcn_readfirstlane(s_claim[3]);
+    if (seq_len == 0) break;
+  }
+  int kv_len_, shift_;
+  if constexpr (Src::kPaged) {
+    kv_len_ = src.kv_len;
+    shift_ = src.kv_len - src.q_len;
+  } else {
+    kv_len_ = seq_len;
+    shift_ = 0;
+  }
+  const int kv_len = kv_len_, shift = shift_;
   // Thread 0: position claimed in this die's queue for the next round.  (Written as a per-thread
   // condition, and read below by every wave, on purpose: the compiler tracks outstanding memory
   // operations per code path, and an atomic that is "maybe still in flight" on some path into
   // the hot loop makes it wait for ALL loads there, which would undo the tile prefetch.)
   int pending_claim = 0x7fffffff;
-  if (threadIdx.x == 0 && !own_empty) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc * kHeadStride], 1);
+  if constexpr (!Src::kPaged) {
+    if (threadIdx.x == 0 && !own_empty) pending_claim = atomicAdd(&a.ctrl->queue_head[xcc * kHeadStride], 1);
+  }
   const int n_tok_tiles = (seq_len + kWaveTileRows - 1) / kWaveTileRows;
   const int n_wave_tiles = n_tok_tiles * a.group;
 
@@ -373,11 +414,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   const int q0 = tok_tile * kWaveTileRows;
   const int f_last = (f0 + kWavesPerItem - 1 < n_wave_tiles ? f0 + kWavesPerItem - 1 : n_wave_tiles - 1);
   // KV tiles (of 64 keys) the workgroup streams
-  const int n_kv_tiles = (seq_len + kKvTileRows - 1) / kKvTileRows;
-  const int causal_keys = (f_last / a.group + 1) * kWaveTileRows;  // keys visible to the item's last query tile
-  const int W = CAUSAL && causal_keys < seq_len ? (causal_keys + kKvTileRows - 1) / kKvTileRows : n_kv_tiles;
+  const int n_kv_tiles = (kv_len + kKvTileRows - 1) / kKvTileRows;
+  const int causal_keys = shift + (f_last / a.group + 1) * kWaveTileRows;  // keys visible to the item's last query tile
+  const int W = CAUSAL && causal_keys < kv_len ? (causal_keys + kKvTileRows - 1) / kKvTileRows : n_kv_tiles;
   // key blocks this wave consumes: keys [0, kv_end)
-  const int kv_end = CAUSAL ? (q0 + kWaveTileRows < seq_len ? q0 + kWaveTileRows : seq_len) : seq_len;
+  const int kv_end = CAUSAL ? (shift + q0 + kWaveTileRows < kv_len ? shift + q0 + kWaveTileRows : kv_len) : kv_len;
   const int NB = active ? (kv_end + kKeyBlock - 1) / kKeyBlock : 0;
 
   // Workgroup iterations: iteration 0 is the prologue (needs K(0)); iteration t >= 1 needs K tile t
@@ -386,16 +427,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // its use into the ring slot freed by the barrier that ended the previous iteration; everything
   // issued in iteration t is needed in iteration t + 1, so each iteration ends with a wait for all
   // of the wave's loads and a barrier.
-  TileLoader<D> k_loader, v_loader;
-  k_loader.template init<false>(a.k, a.k_stride, seq_start, seq_len, kv_head, wave, lane);
-  v_loader.template init<true>(a.v, a.v_stride, seq_start, seq_len, kv_head, wave, lane);
   static_assert(PD == 1 && R == 2, "the iteration-end wait is for everything in flight");
+  // The loaders of the two sources have different shapes: two independent tile loaders for the packed rows, one
+  // gatherer for the pages (a V tile comes from the pages its K tile came from one iteration earlier).
+  std::conditional_t<Src::kPaged, int, TileLoader<D>> k_loader, v_loader;
+  typename Src::template Gather<D> gather;
+  if constexpr (Src::kPaged) {
+    gather.init(src, kv_head, wave, lane);
+  } else {
+    k_loader.template init<false>(a.k, a.k_stride, seq_start, seq_len, kv_head, wave, lane);
+    v_loader.template init<true>(a.v, a.v_stride, seq_start, seq_len, kv_head, wave, lane);
+  }
   // after the issue of iteration t, tile loads 0 .. 2(t+PD) are out; iteration t needs 0 .. 2t
   auto issue_loads = [&](int t) {
-    if (t - 1 + PD < W) v_loader.issue_next(v_ring + ((t - 1 + PD) % R) * G::kTileBytes);
-    if (t + PD < W) k_loader.issue_next(k_ring + ((t + PD) % R) * G::kTileBytes);
+    if constexpr (Src::kPaged) {
+      gather.issue(t - 1 + PD < W, v_ring + ((t - 1 + PD) % R) * G::kTileBytes, t + PD < W, k_ring + ((t + PD) % R) * G::kTileBytes);
+    } else {
+      if (t - 1 + PD < W) v_loader.issue_next(v_ring + ((t - 1 + PD) % R) * G::kTileBytes);
+      if (t + PD < W) k_loader.issue_next(k_ring + ((t + PD) % R) * G::kTileBytes);
+    }
   };
-  k_loader.issue_next(k_ring);
+  if constexpr (Src::kPaged) gather.issue_first(k_ring); else k_loader.issue_next(k_ring);
 
   if (!q_ahead) issue_q_loads(seq_start, seq_len, q0, head, lane);
   // Q fragments (B operand): lane (m, hf) holds query row q0 + 32*qs + m, columns hf*D/2 + 8*s .. +7, as
@@ -408,7 +460,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   for (int qs = 0; qs < QS; ++qs) {
     int row = q0 + 32 * qs + m;
     row = row < seq_len ? row : seq_len - 1;
-    q_lim[qs] = CAUSAL ? row : seq_len - 1;
+    q_lim[qs] = CAUSAL ? shift + row : kv_len - 1;
 #pragma unroll
     for (int s = 0; s < KS; ++s)
       qf[qs][s] = *reinterpret_cast<const qreg_t*>(HYDRA_LDS_BYTE(q_stage + (32 * qs + m) * ROWB + k_swizzle<D>(32 * qs + m, KS * hf + s) * 16));
@@ -495,7 +547,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
         if (key > q_lim[qs]) S[qs][r] = -__builtin_inff();
     }
   };
-  const int min_lim = CAUSAL ? q0 : seq_len - 1;
+  const int min_lim = CAUSAL ? shift + q0 : kv_len - 1;
   auto needs_mask = [&](int j) { return j * kKeyBlock + kKeyBlock - 1 > min_lim; };
 
   // Softmax of a key block whose S holds the raw scores, in 16 * QS halves of an element pair (pair = half / 2:
@@ -645,10 +697,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
 
   __syncthreads();  // K(0) is complete; every wave has taken its Q out of the V ring
   // the rest of the prologue loads: V(0) K(1) V(1) ... K(PD)
+  if constexpr (Src::kPaged) {
+    gather.issue(0 < W, v_ring, 1 < W, k_ring + G::kTileBytes);
+  } else {
 #pragma unroll
-  for (int n = 0; n < PD; ++n) {
-    if (n < W) v_loader.issue_next(v_ring + n * G::kTileBytes);
-    if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
+    for (int n = 0; n < PD; ++n) {
+      if (n < W) v_loader.issue_next(v_ring + n * G::kTileBytes);
+      if (n + 1 < W) k_loader.issue_next(k_ring + (n + 1) * G::kTileBytes);
+    }
   }
 
   // iteration 0: S(0) = K(0) Q^T alone, then S(1) = K(1) Q^T with the vector work of block 0 in its
@@ -711,6 +767,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   wait_all_loads();
   __syncthreads();
   const int pos = __builtin_amdgcn_readfirstlane(pending_claim);  // every wave: the claim has returned (see above)
+  if constexpr (!Src::kPaged)
   if (wave == 0) {
     // (own queue empty: an empty claim is posted, and the top of the next round goes stealing)
     const int idx = pos < own_count ? own_begin + pos : -1;
@@ -827,7 +884,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
   // start its Q loads now.  (When the die's queue has run out the posted claim is empty, and the
   // item stolen at the top of the next round loads its Q there.)
   q_ahead = false;
-  {
+  if constexpr (!Src::kPaged) {
     const int next_len = __builtin_amdgcn_readfirstlane(s_claim[1]);
     if (next_len != 0) {
       const int64_t next_start = __builtin_amdgcn_readfirstlane(s_claim[0]);
@@ -889,7 +946,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroups
       asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen nt\n\ts_nop 1" : : "v"(piece), "v"(off), "s"(rsrc) : "memory");
     }
   }
+  if constexpr (Src::kPaged) break;
   }  // next work item
+  if constexpr (Src::kPaged) {
+    __syncthreads();
+    return s_redo[0] != 0;
+  }
+  return false;
+}
+#endif  // __HIP_DEVICE_COMPILE__
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kWorkgroupsPerCu<D>, kWorkgroupsPerCu<D>))) void attn_fwd_kernel(const AttnArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[TileGeom<D>::kLdsBytes];
+  __shared__ __attribute__((aligned(16))) int s_claim[4];
+  __shared__ __attribute__((aligned(16))) int s_redo[8];
+  attn_item_loop<D, CAUSAL>(a, PackedSource{}, smem, s_claim, s_redo);
 #else
   (void)a;
 #endif

@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_fwd.hpp"
 #include "attn_tiles.hpp"
 
 namespace hydra {
@@ -143,6 +144,129 @@ __device__ __forceinline__ void issue_tile_loads(const TileSlots<D, KEYS, STEP>&
     }
   }
 }
+
+// ---- the wave-tile form on the packed kernel's pipeline --------------------------------------------------
+// A prefill chunk is causal attention whose queries are the LAST q_len positions of a context of kv_len keys,
+// so a group of four wave tiles runs through the packed kernel's item loop (attn_fwd.hpp: software-pipelined
+// key-block steps, fixed softmax reference with a row-sum check) with this source: one item, its K/V tiles
+// gathered from the pages.
+//
+// The gatherer relies on a load instruction's rows (1024 bytes: 4 rows at head_dim 128, 8 at 64) lying in ONE
+// cache block, which holds when the block size is at least that many rows (tiles start at multiples of 64 keys):
+// the block is then the same for all lanes, the load goes through a buffer descriptor that starts at the group's
+// first row and ends with its last valid row (rows past the end of the context arrive as zeros, as in the packed
+// kernel), and a tile needs one table entry per load instruction of the wave.  Those entries are looked up one
+// tile ahead: lane u of the wave fetches the entry of the wave's load u, the iteration-end wait for all loads
+// covers it, and the next iteration's issue reads it lane by lane into scalar registers.  The V tile of an
+// iteration comes from the blocks its K tile came from one iteration earlier, so they are kept.
+// head_dim 80 (a row is not a whole fraction of 1024 bytes) and smaller blocks take the plain loop further down.
+struct PagedSource {
+  static constexpr bool kPaged = true;
+  const PagedArgs* args;
+  const int32_t* table;  // the request's row of the block table
+  int64_t q_start;       // first new token of the request in the packed q / out
+  int q_len, kv_len;     // new tokens, context (new tokens included)
+  int f0, kv_head;       // first flattened wave tile of the group, KV head
+
+  template <int D>
+  struct Gather {
+    using G = TileGeom<D>;
+    static constexpr int kPerWave = G::kLoadInstr / 4;          // load instructions per wave and tile
+    static constexpr int kRowsPerInstr = 1024 / G::kRowBytes;   // rows one load instruction covers
+    static_assert(G::kLoadInstr % 4 == 0 && 1024 % G::kRowBytes == 0 && TileLoader<D>::kUniformStep, "whole rows per instruction");
+    uint32_t k_lo, k_hi, v_lo, v_hi;  // byte address of this KV head's part of cache row 0 (uniform)
+    uint32_t row_bytes;               // bytes between cache rows (uniform)
+    uint32_t k_lane_off, v_lane_off;  // this lane's 16 bytes inside a load instruction's rows
+    const int32_t* table;
+    int kv_len, block_shift, last_block, last_entry, wave;
+    int next_tile;              // the next K tile to issue, whose table entries `pending` holds
+    int32_t pending;            // lane u < kPerWave: table entry of this wave's load u of tile next_tile
+    int32_t v_block[kPerWave];  // blocks of the next V tile to issue (uniform)
+
+    // (first key of the rows of this wave's load u of a tile)
+    __device__ __forceinline__ int first_key(int tile, int u) const { return tile * kKvTileRows + kRowsPerInstr * (wave + 4 * u); }
+
+    __device__ __forceinline__ void lookup(int tile) {
+      // (the lane number is formed here, two instructions, instead of living in a register through the hot loop)
+      const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+      pending = 0;
+      if (lane < kPerWave) {
+        int entry = first_key(tile, lane) >> block_shift;
+        entry = entry < last_entry ? entry : last_entry;  // (tiles past the context are looked up but never loaded)
+        pending = table[entry];
+      }
+    }
+    __device__ __forceinline__ void take(int32_t (&block)[kPerWave]) const {
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) {
+        const int b = __builtin_amdgcn_readlane(pending, u);
+        block[u] = b < 0 ? 0 : (b > last_block ? last_block : b);  // a corrupt table cannot make the loads leave the cache
+      }
+    }
+    __device__ __forceinline__ void issue_tile(int tile, const int32_t (&block)[kPerWave], uint32_t lo, uint32_t hi, uint32_t lane_off,
+                                               uint32_t lds_dst) const {
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) {
+        const int key = first_key(tile, u);
+        const uint32_t slot = ((uint32_t)block[u] << block_shift) + ((uint32_t)key & ((1u << block_shift) - 1u));
+        const uint64_t base = (((uint64_t)hi << 32) | lo) + (uint64_t)slot * row_bytes;
+        int valid = kv_len - key;
+        valid = valid > kRowsPerInstr ? kRowsPerInstr : valid;
+        u32x4_t rsrc;
+        rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+        rsrc[2] = __builtin_amdgcn_readfirstlane(valid > 0 ? (uint32_t)(valid - 1) * row_bytes + D * 2 : 0u);
+        rsrc[3] = 0x00020000u;
+        const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst + (wave + 4 * u) * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(m0), "v"(lane_off), "s"(rsrc));
+      }
+    }
+
+    __device__ __forceinline__ void init(const PagedSource& src, int kv_head, int wave_, int lane) {
+      const PagedArgs& a = *src.args;
+      wave = wave_;
+      __builtin_assume(wave >= 0 && wave < kWavesPerItem);
+      table = src.table;
+      kv_len = src.kv_len;
+      block_shift = a.block_shift;
+      last_block = a.num_blocks - 1;
+      last_entry = a.max_blocks_per_seq - 1;
+      row_bytes = __builtin_amdgcn_readfirstlane((uint32_t)a.n_kv_heads * (D * 2));
+      const uint64_t kb = (uint64_t)(uintptr_t)(a.k_cache + (int64_t)kv_head * D), vb = (uint64_t)(uintptr_t)(a.v_cache + (int64_t)kv_head * D);
+      k_lo = __builtin_amdgcn_readfirstlane((uint32_t)kb);
+      k_hi = __builtin_amdgcn_readfirstlane((uint32_t)(kb >> 32));
+      v_lo = __builtin_amdgcn_readfirstlane((uint32_t)vb);
+      v_hi = __builtin_amdgcn_readfirstlane((uint32_t)(vb >> 32));
+      // (the swizzles repeat from one load instruction of the wave to its next, 16 or 32 rows further on)
+      const int in_instr = lane / G::kChunks, phys = lane % G::kChunks, row = kRowsPerInstr * wave + in_instr;
+      k_lane_off = (uint32_t)in_instr * row_bytes + k_swizzle<D>(row, phys) * 16;
+      v_lane_off = (uint32_t)in_instr * row_bytes + v_swizzle<D>(row, phys) * 16;
+      next_tile = 0;
+      lookup(0);
+    }
+    // K tile 0
+    __device__ __forceinline__ void issue_first(uint32_t k_dst) {
+      take(v_block);
+      issue_tile(0, v_block, k_lo, k_hi, k_lane_off, k_dst);
+      next_tile = 1;
+      lookup(1);
+    }
+    // The V tile that goes with the K tile issued last (if has_v) and the next K tile (if has_k).  Both sets of
+    // table entries are in scalar registers before the first load goes out: the compiler waits for the look-up
+    // where its result is first read, and a wait placed behind tile loads would wait for those as well.
+    __device__ __forceinline__ void issue(bool has_v, uint32_t v_dst, bool has_k, uint32_t k_dst) {
+      if (!has_v && !has_k) return;
+      int32_t k_block[kPerWave];
+      take(k_block);
+      if (has_v) issue_tile(next_tile - 1, v_block, v_lo, v_hi, v_lane_off, v_dst);
+      if (has_k) issue_tile(next_tile, k_block, k_lo, k_hi, k_lane_off, k_dst);
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) v_block[u] = k_block[u];
+      ++next_tile;
+      lookup(next_tile);
+    }
+  };
+};
 
 // A wave's state for 32 * QS query rows (QS sub-tiles of 32) and the arithmetic of one 64-key tile:
 // S^T = K Q^T, mask, online softmax (running maximum, rescaling), O^T += V^T P^T.
@@ -447,7 +571,8 @@ template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_paged_kernel(const PagedArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using G = StageGeom<D>;
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[G::kLdsBytes];
+  constexpr int kLds = G::kLdsBytes > TileGeom<D>::kLdsBytes ? G::kLdsBytes : TileGeom<D>::kLdsBytes;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kLds];
   __shared__ float s_stats[2 * kWavesPerGroup * 64];
 
   // new tokens and context of request b (context cut to what the table can describe; q_len 0: nothing to do,
@@ -582,6 +707,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int n_wave_tiles = n_tok_tiles * a.group;
   if (f0 >= n_wave_tiles) return;  // (cannot happen: the group was counted from these lengths)
   const int shift = kv_len - q_len;  // keys that precede the first new token
+
+  // The group runs on the packed kernel's pipeline when the cache layout allows (see PagedSource); if its row sums
+  // leave that path's range, or the layout does not allow, the plain loop below computes (or recomputes) it.
+  if constexpr (TileLoader<D>::kUniformStep) {
+    if ((1 << a.block_shift) >= PagedSource::Gather<D>::kRowsPerInstr && a.num_blocks <= (0x7fffffff >> a.block_shift)) {
+      PagedSource src;
+      src.args = &a;
+      src.table = table;
+      src.q_start = q_start;
+      src.q_len = q_len;
+      src.kv_len = kv_len;
+      src.f0 = f0;
+      src.kv_head = kv_head;
+      AttnArgs fa;
+      fa.q = a.q;
+      fa.k = nullptr;
+      fa.v = nullptr;
+      fa.out = a.out;
+      fa.q_stride = a.q_stride;
+      fa.k_stride = 0;
+      fa.v_stride = 0;
+      fa.cu_seqlens = nullptr;
+      fa.items = nullptr;
+      fa.ctrl = nullptr;
+      fa.n_q_heads = a.n_q_heads;
+      fa.group = a.group;
+      fa.scale_log2 = a.scale_log2;
+      int* s_claim = reinterpret_cast<int*>(s_stats);  // (unused by a paged item; the redo flag lives behind it)
+      if (!attn_item_loop<D, true>(fa, src, smem, s_claim, s_claim + 8)) return;
+    }
+  }
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

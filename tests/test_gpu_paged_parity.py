@@ -102,6 +102,44 @@ def test_random_hybrid_batches(seed):
     _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
 
 
+PIPELINED_CASES = [
+    # q_lens, kv_lens, Hq, Hkv, d, block_size: prefill chunks whose groups of wave tiles run on the packed kernel's
+    # pipeline (head_dim 64 or 128, a load instruction's rows inside one cache block); contexts of many key tiles,
+    # new tokens that start anywhere inside a key block, last tiles partly filled
+    ([300], [1500], 4, 2, 128, 4),
+    ([300, 1, 77], [1500, 900, 1077], 7, 1, 128, 8),
+    ([512, 512], [2048, 513], 28, 4, 128, 16),
+    ([129, 64, 33], [129 + 31, 64 + 1, 33 + 1000], 8, 2, 64, 8),
+    ([200, 40], [777, 40], 4, 4, 64, 64),
+    ([100], [1000], 2, 1, 128, 256),
+    ([65, 300], [65, 301], 2, 2, 64, 4),               # head_dim 64 with blocks of 4 rows: the plain loop
+]
+
+
+@pytest.mark.parametrize("case", PIPELINED_CASES, ids=lambda c: f"q{'_'.join(map(str, c[0]))}-kv{max(c[1])}-h{c[2]}k{c[3]}-d{c[4]}-b{c[5]}")
+def test_chunks_over_long_contexts_and_block_sizes(case):
+    q_lens, kv_lens, hq, hkv, d, bs = case
+    h = si.HybridBatch("case", q_lens, kv_lens, hq, hkv, d, block_size=bs, seed=7 * len(q_lens) + bs)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_large_scores_in_a_chunk_are_recomputed(d):
+    """Keys planted behind the first key block of a chunk's context whose scores lead the block-0 maximum by far more
+    than the pipelined path's range: the workgroup notices (row sums beyond 2^40 times the reference term) and
+    computes its group of wave tiles again with the plain loop, which rescales at every tile; if it did not, the
+    rows would be inf / NaN or wrong."""
+    h = si.HybridBatch("planted", [100, 1, 257], [400, 300, 257], 4, 2, d, seed=77)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    kc = kc.clone()
+    for b, j in ((0, 50), (0, 350), (2, 200)):       # request, key position (>= 32: not in key block 0)
+        kc[tables[b, j // 16], j % 16] = 64.0        # score = scale * 64 * sum(q): tens of units either way
+    z = h.softmax_scale * 64.0 * _f64(q).sum(axis=-1)
+    assert (z * 1.4427 > 100).sum() > 50
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
+
+
 def test_full_size_hybrid_batch():
     """The benchmark's hybrid batch (96 decode requests + 4 prefill chunks of 512, 28 / 4 heads of 128), whole output."""
     h = si.qwen2vl_hybrid()
