@@ -10,9 +10,9 @@
 //
 // Decomposition: a workgroup of 4 waves takes up to four consecutive wave tiles of one (request, KV
 // head); a wave tile is 32 new tokens of one query head, flattened as f = token_tile * group +
-// head_in_group, so with grouped queries the waves share every K/V tile.  K/V tiles of 64 keys are
-// gathered row by row from the pages (a lane looks its row's page up in the block table, then the
-// 16-byte pieces travel global -> LDS with direct-to-LDS loads) into two stages: tile t + 1 is
+// head_in_group, so with grouped queries the waves share every K/V tile.  In the plain form K/V tiles of
+// 64 keys are gathered row by row from the pages (a lane looks its row's page up in the block table, then
+// the 16-byte pieces travel global -> LDS with direct-to-LDS loads) into two stages: tile t + 1 is
 // fetched while tile t is used.  Scores are kept transposed (S^T = K Q^T, O^T += V^T P^T, as in the
 // packed kernel) and the softmax is the textbook online one: running maximum and rescaling at every
 // tile.  Two workgroups per compute unit.
@@ -20,7 +20,9 @@
 // query heads of a KV head share one tile and the four waves split the keys: see run_packed_rows.
 // When the batch is small for the chip or its contexts are long, the packed-rows form also splits a context
 // over several workgroups and a second, small kernel merges their partial results (see n_splits).
-// This kernel is a first, plain version: no software pipelining inside the wave.
+// Groups of wave tiles run on the packed kernel's software pipeline where the cache layout allows (PagedSource);
+// the loop at the end of attn_paged_kernel is the plain form of the same computation (no pipelining inside the
+// wave, online softmax), which the other layouts and the groups that leave the pipeline's range take.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
