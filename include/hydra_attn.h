@@ -205,7 +205,7 @@ int hydra_kv_cache_write(const void* k, const void* v, int64_t k_token_stride, i
  *        with q_len == 0 (or, invalidly, kv_len < q_len) produces no output.
  *   max_q_len     upper bound on the q_len of the batch (>= 1); sizes the launch.
  *   block_size    a power of two, at least 1 (16 in the paper).   head_dim 64, 80 or 128.
- *   batch and n_kv_heads at most 65535.
+ *   batch and n_kv_heads at most 65535; num_blocks * block_size below 2^31 (HYDRA_ERR_UNSUPPORTED otherwise).
  *   workspace   optional device memory (16-byte aligned; may be NULL with workspace_bytes 0).  With at least
  *        hydra_attn_paged_workspace_bytes(...) bytes, requests with few new tokens (decode steps) have their
  *        context split over several workgroups when the batch alone would not fill the chip or contexts are

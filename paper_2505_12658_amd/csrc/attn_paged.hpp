@@ -104,12 +104,26 @@ template <int D, int KEYS, int STEP>
 struct TileSlots {
   static constexpr int kLoadInstr = KEYS * StageGeom<D>::kRowBytes / 1024;
   static constexpr int kCount = (kLoadInstr + STEP - 1) / STEP;
-  int64_t slot[kCount];
+  int32_t slot[kCount];  // (the host refuses caches of 2^31 rows or more)
 };
 
+// (in two steps for callers that keep other loads in flight across the look-up: the table entries are requested
+// by request_tile_blocks and only touched, which is what the compiler waits for, by slots_from_blocks)
 template <int D, int KEYS, int STEP>
-__device__ __forceinline__ void fetch_tile_slots(TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, const int32_t* table, int first, int lane,
-                                                 int kv_len, int kv0) {
+__device__ __forceinline__ void request_tile_blocks(TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, const int32_t* table, int first, int lane,
+                                                    int kv_len, int kv0) {
+  using G = StageGeom<D>;
+#pragma unroll
+  for (int u = 0; u < TileSlots<D, KEYS, STEP>::kCount; ++u) {
+    const int instr = first + STEP * u;
+    const int row = (instr * 64 + lane) / G::kChunks;
+    int tok = kv0 + row;
+    tok = tok < kv_len ? tok : kv_len - 1;
+    ts.slot[u] = table[tok >> a.block_shift];
+  }
+}
+template <int D, int KEYS, int STEP>
+__device__ __forceinline__ void slots_from_blocks(TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, int first, int lane, int kv_len, int kv0) {
   using G = StageGeom<D>;
   const int in_block = (1 << a.block_shift) - 1;
 #pragma unroll
@@ -118,10 +132,16 @@ __device__ __forceinline__ void fetch_tile_slots(TileSlots<D, KEYS, STEP>& ts, c
     const int row = (instr * 64 + lane) / G::kChunks;
     int tok = kv0 + row;
     tok = tok < kv_len ? tok : kv_len - 1;
-    int block = table[tok >> a.block_shift];
+    int block = ts.slot[u];
     block = block < 0 ? 0 : (block >= a.num_blocks ? a.num_blocks - 1 : block);
-    ts.slot[u] = ((int64_t)block << a.block_shift) + (tok & in_block);
+    ts.slot[u] = (block << a.block_shift) + (tok & in_block);
   }
+}
+template <int D, int KEYS, int STEP>
+__device__ __forceinline__ void fetch_tile_slots(TileSlots<D, KEYS, STEP>& ts, const PagedArgs& a, const int32_t* table, int first, int lane,
+                                                 int kv_len, int kv0) {
+  request_tile_blocks(ts, a, table, first, lane, kv_len, kv0);
+  slots_from_blocks(ts, a, first, lane, kv_len, kv0);
 }
 
 // CPOL: cache-policy bits of the load instructions (2 = nt: lines marked for early replacement, for rows that no
@@ -269,6 +289,40 @@ struct PagedSource {
     }
   };
 };
+
+// The same rows on their way through registers: ordinary loads, which complete in the order they were issued and
+// can be counted, so that a wave can have the NEXT tile's rows in flight while it computes on the current one
+// (direct-to-LDS loads land in no particular order: a wave that uses them can only wait for all of its loads).
+// The rows are written to the stage, in the layout the direct loads would have produced, when their turn comes.
+template <int D, int KEYS>
+struct TileRegs {
+  static constexpr int kLoadInstr = KEYS * StageGeom<D>::kRowBytes / 1024;
+  u32x4_t k[kLoadInstr], v[kLoadInstr];
+};
+template <int D, int KEYS>
+__device__ __forceinline__ void load_tile_regs(TileRegs<D, KEYS>& regs, const TileSlots<D, KEYS, 1>& ts, const PagedArgs& a, int lane, int kv_head) {
+  using G = StageGeom<D>;
+  const int64_t row_elems = (int64_t)a.n_kv_heads * D;
+#pragma unroll
+  for (int u = 0; u < TileRegs<D, KEYS>::kLoadInstr; ++u) {
+    const int flat = u * 64 + lane;
+    const int row = flat / G::kChunks, phys = flat % G::kChunks;
+    const uint16_t* kp = a.k_cache + ts.slot[u] * row_elems + kv_head * D + k_swizzle<D>(row, phys) * 8;
+    const uint16_t* vp = a.v_cache + ts.slot[u] * row_elems + kv_head * D + v_swizzle<D>(row, phys) * 8;
+    // (nt: each key of the context is read by exactly one wave of one workgroup)
+    regs.k[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kp));
+    regs.v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vp));
+  }
+}
+template <int D, int KEYS>
+__device__ __forceinline__ void store_tile_regs(const TileRegs<D, KEYS>& regs, unsigned char* stage, int lane) {
+  constexpr int kTileBytes = KEYS * StageGeom<D>::kRowBytes;
+#pragma unroll
+  for (int u = 0; u < TileRegs<D, KEYS>::kLoadInstr; ++u) {
+    *reinterpret_cast<u32x4_t*>(stage + u * 1024 + lane * 16) = regs.k[u];
+    *reinterpret_cast<u32x4_t*>(stage + kTileBytes + u * 1024 + lane * 16) = regs.v[u];
+  }
+}
 
 // A wave's state for 32 * QS query rows (QS sub-tiles of 32) and the arithmetic of one 64-key tile:
 // S^T = K Q^T, mask, online softmax (running maximum, rescaling), O^T += V^T P^T.
@@ -438,8 +492,9 @@ struct WaveTile {
 // Few new tokens (q_len * group <= 32: decode steps above all): ALL (token, head) pairs of one (request, KV
 // head) form one tile of rows, row = token * group + head_in_group, and the four waves split the KEYS
 // instead of the rows: wave w takes the half tiles (32 keys) w, w + 4, ... into a stage of its own (no
-// workgroup barrier inside the loop, four loads in flight per workgroup), and the four partial results
-// (maximum, sum, unnormalised output per row) are merged through LDS at the end.
+// workgroup barrier inside the loop; a wave's next half tile travels through registers while it computes on
+// the current one, see TileRegs), and the four partial results (maximum, sum, unnormalised output per row)
+// are merged through LDS at the end.
 template <int D>
 __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned char* smem, float* s_stats, const int32_t* table, int64_t q_start,
                                                 int q_len, int kv_len, int kv_head, int request, int split) {
@@ -467,16 +522,25 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   split_range(n_halves, a.halves_per_split, split, h_begin, h_end);
   if (h_begin >= h_end) return;  // an empty share: the combine kernel knows and skips it
   const bool whole = n_halves <= a.halves_per_split;  // the context fits one share: this workgroup writes the output
-  TileSlots<D, kHalfKeys, 1> slots, next_slots;
-  if (h_begin + wave < h_end) fetch_tile_slots(slots, a, table, 0, lane, kv_len, (h_begin + wave) * kHalfKeys);
+  // The rows of half tile h + 4 travel (into registers) while half tile h is computed on, and the block-table
+  // look-up of half tile h + 8 travels behind them; its entries are not touched before the top of the next round.
+  TileSlots<D, kHalfKeys, 1> slots;
+  TileRegs<D, kHalfKeys> regs;
+  if (h_begin + wave < h_end) {
+    fetch_tile_slots(slots, a, table, 0, lane, kv_len, (h_begin + wave) * kHalfKeys);
+    load_tile_regs(regs, slots, a, lane, kv_head);
+    if (h_begin + wave + kWavesPerGroup < h_end) request_tile_blocks(slots, a, table, 0, lane, kv_len, (h_begin + wave + kWavesPerGroup) * kHalfKeys);
+  }
   for (int h = h_begin + wave; h < h_end; h += kWavesPerGroup) {
     const int kv0 = h * kHalfKeys;
-    issue_tile_loads<2>(slots, a, stage, 0, lane, kv_head);  // (each key of the context is read by exactly one wave of one workgroup)
-    // the next half tile's block-table lookup travels together with this one's rows
-    if (h + kWavesPerGroup < h_end) fetch_tile_slots(next_slots, a, table, 0, lane, kv_len, (h + kWavesPerGroup) * kHalfKeys);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    store_tile_regs(regs, stage, lane);
+    if (h + kWavesPerGroup < h_end) {
+      slots_from_blocks(slots, a, 0, lane, kv_len, (h + kWavesPerGroup) * kHalfKeys);
+      load_tile_regs(regs, slots, a, lane, kv_head);
+      if (h + 2 * kWavesPerGroup < h_end) request_tile_blocks(slots, a, table, 0, lane, kv_len, (h + 2 * kWavesPerGroup) * kHalfKeys);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // (the loads go out before the arithmetic, not wherever the scheduler finds room)
     w.template tile<1>(stage, kv0, kv0 + kHalfKeys - 1 > shift);
-    slots = next_slots;
   }
 
   // ---- merge the four waves' partial results ----

@@ -328,7 +328,7 @@ int hydra_attn_paged_fwd(const void* q, void* out, int64_t q_token_stride, const
   if (!q || !out || !k_cache || !v_cache || !block_tables || !cu_seqlens_q || !kv_lens) return HYDRA_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(out) || !aligned16(k_cache) || !aligned16(v_cache)) return HYDRA_ERR_INVALID_ARG;
   if (q_token_stride < (int64_t)n_q_heads * head_dim || (q_token_stride & 7)) return HYDRA_ERR_INVALID_ARG;
-  if (batch > 65535 || n_kv_heads > 65535 || num_blocks > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
+  if (batch > 65535 || n_kv_heads > 65535 || num_blocks * block_size > (int64_t)0x7fffffff) return HYDRA_ERR_UNSUPPORTED;
   if ((int64_t)max_blocks_per_seq * block_size > (int64_t)1 << 30) return HYDRA_ERR_UNSUPPORTED;
   if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return HYDRA_ERR_WORKSPACE;
 

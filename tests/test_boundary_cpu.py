@@ -153,6 +153,7 @@ def test_paged_attn_argument_errors(lib):
     assert call(hq=28, hkv=5) == 1 and call(batch=-1) == 1 and call(mq=0) == 1 and call(mb=0) == 1 and call(nb=0) == 1
     assert call(scale=-1.0) == 1 and call(scale=float("inf")) == 1 and call(scale=float("nan")) == 1
     assert call(d=96) == 2 and call(bs=12) == 2 and call(bs=0) == 2 and call(batch=70000) == 2
+    assert call(nb=1 << 27, bs=16) == 2                         # cache rows are counted in 31 bits
     assert call(ws=None, wsb=64) == 3 and call(ws=ctypes.c_void_p(0x1004), wsb=64) == 3
     # workspace size: nothing for a batch that fills the chip or for short contexts, something for a small batch of long contexts
     assert lib.hydra_attn_paged_workspace_bytes(1024, 4, 128, 64, 16) == 0
