@@ -113,6 +113,8 @@ PIPELINED_CASES = [
     ([200, 40], [777, 40], 4, 4, 64, 64),
     ([100], [1000], 2, 1, 128, 256),
     ([65, 300], [65, 301], 2, 2, 64, 4),               # head_dim 64 with blocks of 4 rows: the plain loop
+    ([5, 33, 9], [7, 40, 9], 7, 1, 128, 16),           # a handful of new tokens whose grouped heads fill more than one tile of rows
+    ([2, 6], [2, 70], 28, 4, 64, 16),                  # one key tile, one key block; a context barely longer than a tile
 ]
 
 
