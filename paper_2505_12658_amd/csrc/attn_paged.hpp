@@ -52,11 +52,11 @@ struct PagedArgs {
   int32_t n_kv_heads;
   int32_t group;     // n_q_heads / n_kv_heads
   float scale_log2;  // softmax_scale * log2(e)
-  // Packed-rows form, long contexts split over workgroups: share s of a context is its half tiles (32 keys
-  // each) [s * halves_per_split, (s + 1) * halves_per_split); n_splits workgroups per (request, KV head), one per
-  // share.  A context that fits one share is done by its first workgroup, which writes `out` itself (the
-  // others leave at once); of a longer one every non-empty share leaves a partial result in `partials`, and
-  // the combine kernel merges them.  n_splits == 1: never split.
+  // Packed-rows form, long contexts split over workgroups: a context of more than halves_per_split half tiles
+  // (32 keys each) is cut into the fewest shares that fit that size, all of (nearly) the same length (share_plan);
+  // n_splits workgroups per (request, KV head), one per share.  A context that fits one share is done by its first
+  // workgroup, which writes `out` itself (the others leave at once); of a longer one every share leaves a partial
+  // result in `partials`, and the combine kernel merges them.  n_splits == 1: never split.
   int32_t n_splits;
   int32_t halves_per_split;
   float* partials;  // [batch, n_kv_heads, n_splits] records of kPartialFloats<D> floats
@@ -69,7 +69,14 @@ struct PagedArgs {
 template <int D>
 constexpr int kPartialFloats = 2 * kRows + kRows * D;
 
-// half tiles [begin, end) of share s of a context of n_halves half tiles (empty past the context's end)
+// How a context of n_halves half tiles is cut: `shares` shares of `per` half tiles (the last one may be shorter);
+// one share when it fits halves_per_split.
+__device__ __forceinline__ void share_plan(int n_halves, int halves_per_split, int& per, int& shares) {
+  const int k = (n_halves + halves_per_split - 1) / halves_per_split;
+  per = k > 1 ? (n_halves + k - 1) / k : n_halves;
+  shares = per > 0 ? (n_halves + per - 1) / per : 0;
+}
+// half tiles [begin, end) of share s (empty past the last share)
 __device__ __forceinline__ void split_range(int n_halves, int per, int s, int& begin, int& end) {
   begin = s * per < n_halves ? s * per : n_halves;
   end = begin + per < n_halves ? begin + per : n_halves;
@@ -519,8 +526,10 @@ __device__ __forceinline__ void run_packed_rows(const PagedArgs& a, unsigned cha
   unsigned char* stage = smem + wave * G::kSlotBytes;
   const int n_halves = (kv_len + kHalfKeys - 1) / kHalfKeys;
   int h_begin, h_end;
-  split_range(n_halves, a.halves_per_split, split, h_begin, h_end);
-  if (h_begin >= h_end) return;  // an empty share: the combine kernel knows and skips it
+  int per_share, n_shares;
+  share_plan(n_halves, a.halves_per_split, per_share, n_shares);
+  split_range(n_halves, per_share, split, h_begin, h_end);
+  if (h_begin >= h_end) return;  // past the context's last share: the combine kernel knows and skips it
   const bool whole = n_halves <= a.halves_per_split;  // the context fits one share: this workgroup writes the output
   // The rows of half tile h + 4 travel (into registers) while half tile h is computed on, and the block-table
   // look-up of half tile h + 8 travels behind them; its entries are not touched before the top of the next round.
@@ -654,7 +663,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int n_rows_wgs = (int)gridDim.x - a.n_tile_wgs;
   if ((int)blockIdx.x < n_rows_wgs) {
     const int r = (int)blockIdx.x;
-    const int pair = r / a.n_splits, split = r - pair * a.n_splits;
+    // (share-major: the workgroups of the first shares, which every request has, lie next to each other and are dealt
+    // to all dies alike; the further shares, some of them empty when contexts differ in length, come behind them)
+    const int pairs = a.batch * a.n_kv_heads;
+    const int split = r / pairs, pair = r - split * pairs;
     b = pair / a.n_kv_heads;
     kv_head = pair - b * a.n_kv_heads;
     int q_len, kv_len;
@@ -880,7 +892,8 @@ __global__ __launch_bounds__(256) void attn_paged_combine_kernel(const PagedArgs
   const int n_rows = q_len * a.group;
   const int n_halves = (kv_len + kKvTileRows / 2 - 1) / (kKvTileRows / 2);
   if (n_halves <= a.halves_per_split) return;  // done by one workgroup, which wrote the output itself
-  const int n_shares = (n_halves + a.halves_per_split - 1) / a.halves_per_split;  // the non-empty shares come first
+  int per_share, n_shares;
+  share_plan(n_halves, a.halves_per_split, per_share, n_shares);
   const float* recs = a.partials + ((int64_t)b * a.n_kv_heads + kv_head) * a.n_splits * kPartialFloats<D>;
   // share s, row r: maximum -> s_max, sum -> s_weight (for now)
   for (int i = threadIdx.x; i < n_shares * kRows; i += 256) {
