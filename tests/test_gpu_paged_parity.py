@@ -213,6 +213,7 @@ SPLIT_CASES = [
     ([4, 1], [3000, 2500], 8, 2, 64),                   # 4 tokens x 4 grouped heads = 16 packed rows, end-aligned mask inside a share
     ([1] * 6, [8192, 100, 4097, 33, 2048, 700], 14, 2, 80),
     ([1, 300], [6000, 900], 28, 4, 128),                # a split decode request next to a chunk in the wave-tile form
+    ([1, 1, 1], [4100, 1089, 545], 8, 2, 128),          # contexts one key past a multiple of the share size (544 keys here)
 ]
 
 
