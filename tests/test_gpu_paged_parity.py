@@ -80,7 +80,7 @@ def test_many_requests_with_scattered_chunks():
     _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_hybrid_batches(seed):
     """Seeded random hybrid batches: decode steps, short and long chunks, whole prefills, empty requests, in
     random order, random head grouping, head_dim and block size; whole output against the oracle."""
@@ -215,6 +215,30 @@ SPLIT_CASES = [
     ([1, 300], [6000, 900], 28, 4, 128),                # a split decode request next to a chunk in the wave-tile form
     ([1, 1, 1], [4100, 1089, 545], 8, 2, 128),          # contexts one key past a multiple of the share size (544 keys here)
 ]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_of_long_contexts(seed):
+    """Seeded random small batches of ragged, long contexts with one or a few new tokens each (the packed-rows form,
+    contexts cut into shares of equal length over several workgroups and merged), random head grouping, head_dim and
+    block size; whole output against the oracle."""
+    rng = np.random.default_rng(3000 + seed)
+    hq, hkv = [(1, 1), (4, 1), (4, 2), (7, 1), (8, 8), (28, 4), (16, 2)][int(rng.integers(7))]
+    d = [64, 80, 128][int(rng.integers(3))]
+    bs = [4, 16, 32, 64][int(rng.integers(4))]
+    g = hq // hkv
+    top = [1500, 3000, 6000][int(rng.integers(3))]
+    q_lens, kv_lens = [], []
+    for _ in range(int(rng.integers(1, 6))):
+        ql = int(rng.integers(1, max(2, 32 // g + 1))) if rng.random() < 0.9 else 0
+        kv = int(rng.integers(ql, top)) if rng.random() < 0.7 else top - int(rng.integers(0, 40))
+        q_lens.append(ql)
+        kv_lens.append(max(kv, ql))
+    if sum(q_lens) == 0:
+        q_lens[0], kv_lens[0] = 1, top
+    h = si.HybridBatch("long", q_lens, kv_lens, hq, hkv, d, block_size=bs, seed=seed)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    _check(_run_gpu(h, q, kc, vc, tables), _want(h, q, kc, vc, tables))
 
 
 @pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: f"q{'_'.join(map(str, c[0]))}-kv{max(c[1])}-h{c[2]}k{c[3]}-d{c[4]}")
