@@ -17,6 +17,9 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never allocates,
  *     frees or keeps them.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and the call returns without synchronising with the device.
+ *   - A call only launches kernels on `stream`: no memory is allocated, set or copied, and lengths,
+ *     block tables and slot mappings are read on the device when the kernels run.  A call may therefore
+ *     be recorded into a HIP graph; a replay acts on whatever the recorded buffers hold at that time.
  *   - bf16 means the upper 16 bits of an IEEE binary32 value.
  *   - Return value: a hydra_status.  Argument errors are detected on the host before anything
  *     is launched; nothing is written in that case.  The library neither prints nor aborts.
