@@ -257,3 +257,48 @@ def test_contexts_split_over_workgroups(case):
     # a workspace too small for the preferred number of shares still gives the right answer (fewer shares)
     small = torch.empty(hydra.hydra_attn_paged_workspace_bytes(h.batch, hkv, d, tables.shape[1], 16) // 3, dtype=torch.uint8, device="cuda:0")
     _check(_run_gpu(h, q, kc, vc, tables, workspace=small), want)
+
+
+def test_requests_pages_move_to_another_cache():
+    """What a migration between instances does to a request on the sending and on the receiving GPU (Section 4.3:
+    its cache pages are copied, its page table is rewritten), done here between two caches on one GPU with the
+    paged-cache copy calls, one row per cache block: the pages of every request are gathered into one contiguous
+    buffer (what would travel), written into other blocks of a second cache, and attention over the second cache with
+    the rewritten block table gives the same output bit for bit; blocks of the second cache that received nothing
+    keep their contents."""
+    import paper_2505_12658_amd as hydra
+
+    dev = torch.device("cuda:0")
+    h = si.HybridBatch("move", [1, 70, 1, 3], [300, 200, 77, 19], 8, 2, 128, seed=55)
+    q, kc, vc, tables = si.make_paged_inputs(h)
+    qd, kcd, vcd = q.to(dev), kc.to(dev), vc.to(dev)
+    cu = torch.from_numpy(h.cu_seqlens_q).to(dev)
+    kv = torch.tensor(h.kv_lens, dtype=torch.int32, device=dev)
+    before = hydra.hydra_attn_paged_fwd(qd, kcd, vcd, torch.from_numpy(tables).to(dev), cu, kv, h.max_q_len, h.softmax_scale)
+    # the blocks that hold context, request by request, and their new places in a cache of another size
+    bs = 16
+    used = [tables[b, : (k + bs - 1) // bs] for b, k in enumerate(h.kv_lens)]
+    src = np.concatenate(used).astype(np.int64)
+    n_dst = len(src) + 13
+    rng = np.random.default_rng(5)
+    dst = rng.permutation(n_dst)[: len(src)].astype(np.int64)
+    tables2 = np.zeros_like(tables)
+    at = 0
+    for b, u in enumerate(used):
+        tables2[b, : len(u)] = dst[at : at + len(u)]
+        at += len(u)
+    row = bs * 2 * 128
+    sentinel = 1.5
+    kc2 = torch.full((n_dst, bs, 2, 128), sentinel, dtype=torch.bfloat16, device=dev)
+    vc2 = torch.full((n_dst, bs, 2, 128), -sentinel, dtype=torch.bfloat16, device=dev)
+    srcd, dstd = torch.from_numpy(src).to(dev), torch.from_numpy(dst).to(dev)
+    for cache, cache2 in ((kcd, kc2), (vcd, vc2)):
+        packed = torch.empty((len(src), row), dtype=torch.bfloat16, device=dev)
+        hydra.hydra_page_cache_gather(cache.view(cache.shape[0], row), srcd, packed)
+        hydra.hydra_page_cache_write(packed, cache2.view(n_dst, row), dstd)
+    after = hydra.hydra_attn_paged_fwd(qd, kc2, vc2, torch.from_numpy(tables2).to(dev), cu, kv, h.max_q_len, h.softmax_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(before.view(torch.int16), after.view(torch.int16))
+    _check(after, _want(h, q, kc, vc, tables))
+    untouched = np.setdiff1d(np.arange(n_dst), dst)
+    assert (kc2[torch.from_numpy(untouched).to(dev)] == sentinel).all() and (vc2[torch.from_numpy(untouched).to(dev)] == -sentinel).all()
